@@ -1,0 +1,151 @@
+/*
+ * vitenc — packed vision-transformer image encoder for MI355X (gfx950), C ABI.
+ *
+ * The operation: the image-encoding stage of a large multimodal model served as its
+ * own instance (paper Sec. 2 "Image Encoding"; Sec. 4 "Image Instances").  Uniform-size
+ * image tiles go in, image-token embeddings come out.  Images of a request do not
+ * attend to each other (paper Sec. 1; Sec. 3.1 "Compute Characteristics"), so the images
+ * of many requests are packed into one launch; attention is confined to a tile (local
+ * layers) or to the tiles of one image (global layers) and never crosses images.
+ *
+ * All functions return a status and never throw or abort across the ABI.
+ * The message for the last failure on the calling thread is vit_last_error().
+ */
+#ifndef VITENC_H
+#define VITENC_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+#pragma GCC visibility push(default)
+
+typedef struct vit_encoder vit_encoder_t; /* opaque; owned by the library */
+
+typedef enum {
+  VIT_OK = 0,
+  VIT_EINVAL = -1,    /* bad argument or inconsistent shapes; nothing was launched        */
+  VIT_ENOMEM = -2,    /* host or device allocation failed (create only)                   */
+  VIT_ECAPACITY = -3, /* output or workspace buffer too small; nothing was launched       */
+  VIT_EDEVICE = -4    /* a HIP call failed; vit_last_error() carries the HIP error string */
+} vit_status_t;
+
+enum { VIT_DTYPE_FP32 = 0, VIT_DTYPE_BF16 = 1 };
+
+/*
+ * Encoder shape.  Tokens per tile T = floor(image_size/patch_size)^2 + has_cls
+ * (paper Table 1: 560/14 with CLS -> 1601; 384/14 without -> 729).
+ */
+typedef struct {
+  int32_t image_size;    /* S: tiles are S x S pixels                                           */
+  int32_t patch_size;    /* p                                                                   */
+  int32_t channels;      /* C (3)                                                               */
+  int32_t hidden;        /* D, divisible by heads                                               */
+  int32_t heads;         /* H; head dim D/H must be <= 128 and a multiple of 8                  */
+  int32_t mlp;           /* M: width of the block MLP                                           */
+  int32_t layers_local;  /* blocks whose attention segment is one tile                          */
+  int32_t layers_global; /* following blocks whose attention segment is all tiles of one image  */
+  int32_t has_cls;       /* 1: a learned CLS row precedes the patches of every tile             */
+  int32_t final_ln;      /* 1: LayerNorm after the last block                                   */
+  float ln_eps;          /* added to the biased variance                                        */
+  int32_t proj_layers;   /* 0, 1 or 2 linear layers after the encoder, GELU between them        */
+  int32_t proj_dims[2];  /* output width of each projector layer                                */
+  int32_t dtype;         /* VIT_DTYPE_FP32: fp32 arithmetic and output;                         */
+                         /* VIT_DTYPE_BF16: bf16 matrix operands, fp32 accumulation and         */
+                         /* residual stream, bf16 output                                        */
+} vit_config_t;
+
+/*
+ * Number of fp32 values vit_encoder_create expects for `cfg` (0 if cfg is invalid).
+ * Order of the flat buffer, every matrix row-major [out_features, in_features]:
+ *   patch_w [D, C*p*p] (index c*p*p + py*p + px), patch_b [D], cls [D] (if has_cls),
+ *   pos [T, D];
+ *   per block: ln1_g, ln1_b [D]; wqkv [3D, D] (rows: all of Q, then K, then V; head h is
+ *   rows h*dh..), bqkv [3D]; wo [D, D], bo [D]; ln2_g, ln2_b [D]; w1 [M, D], b1 [M];
+ *   w2 [D, M], b2 [D];
+ *   lnf_g, lnf_b [D] (if final_ln); per projector layer: w [out, in], b [out].
+ */
+size_t vit_weight_count(const vit_config_t* cfg);
+
+/*
+ * Build an encoder on HIP device `device`.
+ *   weights   HOST pointer, n_weights fp32 values in the order above.  The library
+ *             converts (round-to-nearest-even to bf16 when dtype is bf16), pads and uploads
+ *             them; the caller keeps ownership and may free the buffer on return.
+ *   out       receives the handle; release it with vit_encoder_destroy.
+ * Errors: VIT_EINVAL (null pointers, invalid cfg, n_weights != vit_weight_count),
+ *         VIT_ENOMEM, VIT_EDEVICE.  *out is NULL on failure.
+ */
+vit_status_t vit_encoder_create(const vit_config_t* cfg, const float* weights, size_t n_weights,
+                                int device, vit_encoder_t** out);
+
+/*
+ * Pure host function: what a launch over n_tiles tiles grouped into n_images images
+ * produces and needs.  n_tokens = n_tiles * T; out_dim = last projector width, or D;
+ * workspace_bytes is an upper bound valid for any grouping of n_tiles tiles into
+ * n_images >= 1 images.  Any output pointer may be NULL.
+ */
+vit_status_t vit_encoder_query(const vit_encoder_t* enc, int32_t n_tiles, int32_t n_images,
+                               int64_t* n_tokens, int32_t* out_dim, size_t* out_bytes,
+                               size_t* workspace_bytes);
+
+/*
+ * Encode one packed batch (patchify + position add, all blocks, final LN, projector).
+ *   pixels              DEVICE, [n_tiles, C, S, S] fp32, already normalised (preprocessing
+ *                       is the CPU stage before this one, paper Sec. 2).
+ *   images_per_request  HOST, [n_requests], each >= 0 (0 = text-only request, which owns
+ *                       an empty token range); sum = n_images.
+ *   tile_offsets        HOST, [n_images + 1], prefix sum of tiles per image:
+ *                       [0] = 0, strictly increasing, last = n_tiles.
+ *   out_tokens          DEVICE, [n_tiles * T, out_dim] row-major, bf16 or fp32 per dtype,
+ *                       in input tile order; out_capacity_bytes is its size.
+ *   request_token_offsets  HOST, optional [n_requests + 1]: first token row of each request.
+ *   workspace           DEVICE scratch of at least vit_encoder_query's workspace_bytes,
+ *                       256-byte aligned; contents are undefined before and after.
+ *   stream              hipStream_t (NULL = default stream).
+ * The call is asynchronous on `stream`: host arrays are consumed before it returns, device
+ * buffers must stay valid until the stream has drained.  The library keeps no reference to
+ * caller buffers afterwards and never frees them.  One handle may have any number of
+ * launches queued on ONE stream; concurrent use from several threads or streams is not
+ * supported.  n_requests = 0 or n_tiles = 0 is a successful no-op.
+ * Errors: VIT_EINVAL (null pointers, negative counts, an image with no tiles),
+ *         VIT_ECAPACITY (nothing launched), VIT_EDEVICE.
+ */
+vit_status_t vit_encode_packed(vit_encoder_t* enc, const float* pixels,
+                               const int32_t* images_per_request, int32_t n_requests,
+                               const int32_t* tile_offsets, void* out_tokens,
+                               size_t out_capacity_bytes, int64_t* request_token_offsets,
+                               void* workspace, size_t workspace_bytes, void* stream);
+
+/* Free device weights and the handle.  NULL is allowed.  The caller must have drained
+ * every stream the handle was used on. */
+void vit_encoder_destroy(vit_encoder_t* enc);
+
+/* Message of the last failure on this thread (static storage, never NULL). */
+const char* vit_last_error(void);
+
+/*
+ * Timing aid: average device time in milliseconds of each kernel family over all
+ * vit_encode_packed calls since the last reset, measured with HIP events on the launch
+ * stream.  Off by default (it adds events to the stream); enable != 0 switches it on and
+ * resets the counters.  vit_profile_read synchronises the recorded events and fills
+ * ms[VIT_PROF_COUNT] and launches[VIT_PROF_COUNT] with total milliseconds and number of
+ * kernel launches per family.
+ */
+enum {
+  VIT_PROF_PATCHIFY = 0, /* patch gather + CLS rows                 */
+  VIT_PROF_GEMM = 1,     /* all matrix products incl. patch GEMM    */
+  VIT_PROF_LAYERNORM = 2,
+  VIT_PROF_ATTENTION = 3,
+  VIT_PROF_COUNT = 4
+};
+vit_status_t vit_profile_enable(vit_encoder_t* enc, int enable);
+vit_status_t vit_profile_read(vit_encoder_t* enc, double* ms, int64_t* launches);
+
+#pragma GCC visibility pop
+#ifdef __cplusplus
+}
+#endif
+#endif /* VITENC_H */

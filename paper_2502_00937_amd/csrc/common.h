@@ -1,0 +1,131 @@
+// Shared device helpers and the launcher interface between the host plan and the kernels.
+// gfx950 only: wave64, MFMA with 8-element bf16 operands.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace vitenc {
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+
+typedef uint16_t bf16_t;  // storage type of a bfloat16 value in global memory
+
+// fp32 -> bf16, round to nearest even (finite inputs; NaN stays NaN).
+__host__ __device__ inline bf16_t f32_to_bf16(float f) {
+  union { float f; uint32_t u; } v;
+  v.f = f;
+  if ((v.u & 0x7FFFFFFFu) > 0x7F800000u) return (bf16_t)((v.u >> 16) | 0x40u);
+  v.u += 0x7FFFu + ((v.u >> 16) & 1u);
+  return (bf16_t)(v.u >> 16);
+}
+__host__ __device__ inline float bf16_to_f32(bf16_t h) {
+  union { float f; uint32_t u; } v;
+  v.u = ((uint32_t)h) << 16;
+  return v.f;
+}
+// two fp32 -> packed pair of bf16 (low half = a)
+__device__ inline uint32_t pack_bf16x2(float a, float b) {
+  return (uint32_t)f32_to_bf16(a) | ((uint32_t)f32_to_bf16(b) << 16);
+}
+
+// Element-type traits for the two arithmetic modes.
+template <typename T> struct Elem;
+template <> struct Elem<float> {
+  __device__ static inline float load(const float* p) { return *p; }
+  __device__ static inline void store(float* p, float v) { *p = v; }
+};
+template <> struct Elem<bf16_t> {
+  __device__ static inline float load(const bf16_t* p) { return bf16_to_f32(*p); }
+  __device__ static inline void store(bf16_t* p, float v) { *p = f32_to_bf16(v); }
+};
+
+// Exact-form GELU z/2 (1 + erf(z / sqrt 2)).
+__device__ inline float gelu_erf(float z) { return 0.5f * z * (1.0f + erff(z * 0.70710678118654752440f)); }
+
+// ---- epilogues of the matrix products ---------------------------------------------------
+enum Epilogue {
+  EPI_BIAS = 0,           // out[r, c] = acc + bias[c]                         (activation type)
+  EPI_BIAS_GELU = 1,      // out[r, c] = gelu(acc + bias[c])                   (activation type)
+  EPI_BIAS_RESIDUAL = 2,  // resid[r, c] += acc + bias[c]                      (fp32, in place)
+  EPI_PATCH = 3           // resid[tile*T + cls + patch, c] = acc + bias[c] + pos[cls + patch, c]
+};
+
+struct GemmArgs {
+  const void* A;      // [M_pad, lda] activations, K contiguous
+  const void* W;      // [N_pad, ldw] weights, K contiguous (zero padded)
+  const float* bias;  // [N_pad]
+  void* out;          // activation-type output (EPI_BIAS, EPI_BIAS_GELU)
+  float* resid;       // fp32 residual stream (EPI_BIAS_RESIDUAL, EPI_PATCH)
+  const float* pos;   // [T, ld_resid] position table (EPI_PATCH)
+  int M;              // valid rows
+  int N;              // valid output columns (stores are masked beyond)
+  int K;              // padded contraction length, multiple of 64
+  int lda, ldw, ldo;  // leading dimensions in elements (ldo: of out or resid)
+  int patches;        // EPI_PATCH: patches per tile P
+  int tokens;         // EPI_PATCH: tokens per tile T
+  int cls;            // EPI_PATCH: 1 if a CLS row precedes the patches
+  int epilogue;
+};
+
+// Applies one epilogue to a single accumulator; the caller guarantees row < M and col < N.
+template <int EPI, typename OutT>
+__device__ __forceinline__ void epilogue_store(const GemmArgs& a, int row, int col, float acc) {
+  float v = acc + a.bias[col];
+  if constexpr (EPI == EPI_BIAS) {
+    Elem<OutT>::store((OutT*)a.out + (size_t)row * a.ldo + col, v);
+  } else if constexpr (EPI == EPI_BIAS_GELU) {
+    Elem<OutT>::store((OutT*)a.out + (size_t)row * a.ldo + col, gelu_erf(v));
+  } else if constexpr (EPI == EPI_BIAS_RESIDUAL) {
+    float* p = a.resid + (size_t)row * a.ldo + col;
+    *p += v;
+  } else {  // EPI_PATCH
+    int tile = row / a.patches;
+    int tok = a.cls + (row - tile * a.patches);
+    a.resid[((size_t)tile * a.tokens + tok) * a.ldo + col] = v + a.pos[(size_t)tok * a.ldo + col];
+  }
+}
+
+// Attention work item: one block of query rows inside one segment.
+struct AttnWork {
+  int32_t q0;         // first query row (global token row)
+  int32_t seg_start;  // first key row of the segment
+  int32_t seg_len;    // number of keys in the segment
+};
+
+struct AttnArgs {
+  const void* qkv;  // [rows, ld_qkv]: Q heads, then K heads, then V heads, each head dh_pad wide
+  void* out;        // [rows, ld_o]: head h at columns h*dh_pad
+  const AttnWork* work;
+  int n_work;
+  int heads;
+  int dh;      // true head dim (for the logit scale)
+  int dh_pad;  // padded head dim used in memory
+  int ld_qkv, ld_o;
+};
+
+// ---- launchers (defined in the .hip files) ----------------------------------------------
+// bf16 MFMA path
+hipError_t launch_gemm_bf16(const GemmArgs& a, hipStream_t s);
+hipError_t launch_attention_bf16(const AttnArgs& a, hipStream_t s);
+// fp32 path
+hipError_t launch_gemm_f32(const GemmArgs& a, hipStream_t s);
+hipError_t launch_attention_f32(const AttnArgs& a, hipStream_t s);
+// shared, templated on activation type inside
+hipError_t launch_layernorm(const float* x, int ldx, void* out, int ldo, int out_cols, const float* gamma,
+                            const float* beta, float eps, int rows, int D, int normalize, int out_bf16,
+                            hipStream_t s);
+hipError_t launch_patch_gather(const float* pixels, void* patches, int ld, int n_tiles, int C, int S, int p, int g,
+                               int Kpad, int out_bf16, hipStream_t s);
+hipError_t launch_cls_rows(float* x, int ldx, const float* cls, const float* pos, int n_tiles, int T, int D,
+                           hipStream_t s);
+hipError_t launch_fill_zero_cols(void* buf, int ld, int rows, int col0, int col1, int elem_bytes, hipStream_t s);
+
+int attention_q_block(int dtype_bf16);  // query rows per work item for each path
+int gemm_row_pad();                     // row padding every activation buffer must have
+
+}  // namespace vitenc

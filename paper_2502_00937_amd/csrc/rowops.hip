@@ -1,0 +1,190 @@
+// Memory-bound row kernels: LayerNorm (fp32 residual stream -> matrix operand), patch
+// gather, CLS rows, padding fill.  All are HBM-bound; each element is read once and
+// written once with 16-byte accesses where the layout allows.
+#include "common.h"
+
+namespace vitenc {
+
+namespace {
+
+__device__ inline float wave_sum(float v) {
+#pragma unroll
+  for (int off = 32; off > 0; off >>= 1) v += __shfl_xor(v, off, 64);
+  return v;
+}
+
+// One wave per token row.  Two passes over registers: mean, then biased variance of the
+// centred values (no E[x^2] - mean^2 cancellation).  Columns D..out_cols-1 of the output
+// are written as zero so the row can feed a K-padded matrix product.
+// NORMALIZE = 0 turns the kernel into a plain fp32 -> OutT conversion.
+template <typename OutT, int MAXV, int NORMALIZE>
+__global__ __launch_bounds__(256) void layernorm_kernel(const float* __restrict__ x, int ldx, OutT* __restrict__ out,
+                                                        int ldo, int out_cols, const float* __restrict__ gamma,
+                                                        const float* __restrict__ beta, float eps, int rows, int D) {
+  const int lane = threadIdx.x & 63;
+  const int row = blockIdx.x * 4 + (threadIdx.x >> 6);
+  if (row >= rows) return;
+  const float* xr = x + (size_t)row * ldx;
+  f32x4 v[MAXV];
+  float s = 0.f;
+#pragma unroll
+  for (int i = 0; i < MAXV; ++i) {
+    const int c = (i * 64 + lane) * 4;
+    if (c < D) {
+      v[i] = *(const f32x4*)(xr + c);
+      s += (v[i][0] + v[i][1]) + (v[i][2] + v[i][3]);
+    } else {
+      v[i] = f32x4{0.f, 0.f, 0.f, 0.f};
+    }
+  }
+  float mean = 0.f, rstd = 1.f;
+  if (NORMALIZE) {
+    mean = wave_sum(s) / (float)D;
+    float q = 0.f;
+#pragma unroll
+    for (int i = 0; i < MAXV; ++i) {
+      const int c = (i * 64 + lane) * 4;
+      if (c < D) {
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+          const float d = v[i][e] - mean;
+          q += d * d;
+        }
+      }
+    }
+    rstd = rsqrtf(wave_sum(q) / (float)D + eps);
+  }
+  OutT* orow = out + (size_t)row * ldo;
+#pragma unroll
+  for (int i = 0; i < MAXV; ++i) {
+    const int c = (i * 64 + lane) * 4;
+    if (c >= out_cols) continue;
+    float y[4] = {0.f, 0.f, 0.f, 0.f};
+    if (c < D) {
+      if (NORMALIZE) {
+        const f32x4 g = *(const f32x4*)(gamma + c), b = *(const f32x4*)(beta + c);
+#pragma unroll
+        for (int e = 0; e < 4; ++e) y[e] = (v[i][e] - mean) * rstd * g[e] + b[e];
+      } else {
+#pragma unroll
+        for (int e = 0; e < 4; ++e) y[e] = v[i][e];
+      }
+    }
+    if constexpr (sizeof(OutT) == 2) {
+      u32x2 pk = {pack_bf16x2(y[0], y[1]), pack_bf16x2(y[2], y[3])};
+      *(u32x2*)(orow + c) = pk;
+    } else {
+      *(f32x4*)(orow + c) = f32x4{y[0], y[1], y[2], y[3]};
+    }
+  }
+}
+
+// patches[(tile*g*g + gy*g + gx), c*p*p + py*p + px] = pixels[tile, c, gy*p+py, gx*p+px];
+// columns K..Kpad-1 are zero.  One thread per output element, column fastest (coalesced writes;
+// reads are runs of p contiguous pixels).
+template <typename OutT>
+__global__ __launch_bounds__(256) void patch_gather_kernel(const float* __restrict__ px, OutT* __restrict__ out, int ld,
+                                                           long total, int C, int S, int p, int g, int K, int Kpad) {
+  const long idx = (long)blockIdx.x * 256 + threadIdx.x;
+  if (idx >= total) return;
+  const int col = (int)(idx % Kpad);
+  const long row = idx / Kpad;
+  float v = 0.f;
+  if (col < K) {
+    const int P = g * g;
+    const long tile = row / P;
+    const int pi = (int)(row - tile * P), gy = pi / g, gx = pi - gy * g;
+    const int c = col / (p * p), r = col - c * p * p, py = r / p, pxx = r - py * p;
+    v = px[((tile * C + c) * S + (gy * p + py)) * (long)S + gx * p + pxx];
+  }
+  Elem<OutT>::store(out + row * ld + col, v);
+}
+
+// x[tile*T, :] = cls + pos[0, :]
+__global__ __launch_bounds__(256) void cls_rows_kernel(float* __restrict__ x, int ldx, const float* __restrict__ cls,
+                                                       const float* __restrict__ pos, int n_tiles, int T, int D) {
+  const long idx = (long)blockIdx.x * 256 + threadIdx.x;
+  if (idx >= (long)n_tiles * D) return;
+  const int c = (int)(idx % D);
+  const long tile = idx / D;
+  x[tile * T * ldx + c] = cls[c] + pos[c];
+}
+
+template <typename T>
+__global__ __launch_bounds__(256) void fill_zero_cols_kernel(T* buf, int ld, long rows, int col0, int ncols) {
+  const long idx = (long)blockIdx.x * 256 + threadIdx.x;
+  if (idx >= rows * ncols) return;
+  buf[(idx / ncols) * ld + col0 + (int)(idx % ncols)] = (T)0;
+}
+
+template <typename OutT, int NORMALIZE>
+hipError_t ln_dispatch(const float* x, int ldx, void* out, int ldo, int out_cols, const float* gamma, const float* beta,
+                       float eps, int rows, int D, hipStream_t s) {
+  const dim3 grid((rows + 3) / 4), block(256);
+  const int need = (out_cols + 255) / 256;  // float4 slots per lane
+#define VIT_LN(MAXV)                                                                                              \
+  hipLaunchKernelGGL((layernorm_kernel<OutT, MAXV, NORMALIZE>), grid, block, 0, s, x, ldx, (OutT*)out, ldo, out_cols, \
+                     gamma, beta, eps, rows, D)
+  if (need <= 1) VIT_LN(1);
+  else if (need <= 2) VIT_LN(2);
+  else if (need <= 4) VIT_LN(4);
+  else if (need <= 5) VIT_LN(5);
+  else if (need <= 8) VIT_LN(8);
+  else if (need <= 16) VIT_LN(16);
+  else return hipErrorInvalidValue;
+#undef VIT_LN
+  return hipGetLastError();
+}
+
+}  // namespace
+
+hipError_t launch_layernorm(const float* x, int ldx, void* out, int ldo, int out_cols, const float* gamma,
+                            const float* beta, float eps, int rows, int D, int normalize, int out_bf16,
+                            hipStream_t s) {
+  if (rows <= 0) return hipSuccess;
+  if (D % 4 != 0 || out_cols % 4 != 0 || ldx % 4 != 0 || ldo % 4 != 0 || out_cols < D) return hipErrorInvalidValue;
+  if (out_bf16) {
+    return normalize ? ln_dispatch<bf16_t, 1>(x, ldx, out, ldo, out_cols, gamma, beta, eps, rows, D, s)
+                     : ln_dispatch<bf16_t, 0>(x, ldx, out, ldo, out_cols, gamma, beta, eps, rows, D, s);
+  }
+  return normalize ? ln_dispatch<float, 1>(x, ldx, out, ldo, out_cols, gamma, beta, eps, rows, D, s)
+                   : ln_dispatch<float, 0>(x, ldx, out, ldo, out_cols, gamma, beta, eps, rows, D, s);
+}
+
+hipError_t launch_patch_gather(const float* pixels, void* patches, int ld, int n_tiles, int C, int S, int p, int g,
+                               int Kpad, int out_bf16, hipStream_t s) {
+  const long total = (long)n_tiles * g * g * Kpad;
+  if (total <= 0) return hipSuccess;
+  const dim3 grid((unsigned)((total + 255) / 256)), block(256);
+  const int K = C * p * p;
+  if (out_bf16)
+    hipLaunchKernelGGL(patch_gather_kernel<bf16_t>, grid, block, 0, s, pixels, (bf16_t*)patches, ld, total, C, S, p, g,
+                       K, Kpad);
+  else
+    hipLaunchKernelGGL(patch_gather_kernel<float>, grid, block, 0, s, pixels, (float*)patches, ld, total, C, S, p, g, K,
+                       Kpad);
+  return hipGetLastError();
+}
+
+hipError_t launch_cls_rows(float* x, int ldx, const float* cls, const float* pos, int n_tiles, int T, int D,
+                           hipStream_t s) {
+  const long total = (long)n_tiles * D;
+  if (total <= 0) return hipSuccess;
+  hipLaunchKernelGGL(cls_rows_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, s, x, ldx, cls, pos, n_tiles,
+                     T, D);
+  return hipGetLastError();
+}
+
+hipError_t launch_fill_zero_cols(void* buf, int ld, int rows, int col0, int col1, int elem_bytes, hipStream_t s) {
+  const int ncols = col1 - col0;
+  const long total = (long)rows * ncols;
+  if (total <= 0) return hipSuccess;
+  const dim3 grid((unsigned)((total + 255) / 256)), block(256);
+  if (elem_bytes == 2)
+    hipLaunchKernelGGL(fill_zero_cols_kernel<bf16_t>, grid, block, 0, s, (bf16_t*)buf, ld, (long)rows, col0, ncols);
+  else
+    hipLaunchKernelGGL(fill_zero_cols_kernel<float>, grid, block, 0, s, (float*)buf, ld, (long)rows, col0, ncols);
+  return hipGetLastError();
+}
+
+}  // namespace vitenc

@@ -1,0 +1,578 @@
+// C ABI of the packed ViT encoder: validation, weight re-layout, segment planning,
+// workspace carving and the launch sequence.  No arithmetic of the encoder happens on the
+// host; every step runs in the kernels of this library.
+#include "../../include/vitenc.h"
+
+#include <algorithm>
+#include <cmath>
+#include <cstdarg>
+#include <cstdio>
+#include <cstring>
+#include <new>
+#include <vector>
+
+#include "common.h"
+
+using namespace vitenc;
+
+namespace {
+
+thread_local char g_err[512] = "";
+
+vit_status_t fail(vit_status_t st, const char* fmt, ...) {
+  va_list ap;
+  va_start(ap, fmt);
+  vsnprintf(g_err, sizeof(g_err), fmt, ap);
+  va_end(ap);
+  return st;
+}
+
+#define HIP_TRY(expr)                                                                       \
+  do {                                                                                      \
+    hipError_t e_ = (expr);                                                                 \
+    if (e_ != hipSuccess) return fail(VIT_EDEVICE, "%s: %s", #expr, hipGetErrorString(e_)); \
+  } while (0)
+
+inline int64_t round_up(int64_t v, int64_t m) { return (v + m - 1) / m * m; }
+
+// Shapes derived from a config (all in elements).
+struct Dims {
+  int S, p, C, g, P, T, Kp, Kp_pad;
+  int D, H, dh, dhp, M;
+  int Dp, QKVN, Op, Mp;
+  int L, L_loc;
+  int proj_layers, proj_dims[2], proj0_ld;
+  int out_dim;
+  int bf16;  // 1: bf16 operands, 0: fp32
+  int es;    // bytes per activation element
+  float eps;
+  int has_cls, final_ln;
+};
+
+bool derive(const vit_config_t* c, Dims* d, const char** why) {
+  *why = "";
+  if (!c) { *why = "cfg is NULL"; return false; }
+  if (c->image_size <= 0 || c->patch_size <= 0 || c->channels <= 0 || c->patch_size > c->image_size) {
+    *why = "image_size, patch_size, channels must be positive and patch_size <= image_size";
+    return false;
+  }
+  if (c->hidden <= 0 || c->heads <= 0 || c->hidden % c->heads != 0) { *why = "hidden must be a positive multiple of heads"; return false; }
+  const int dh = c->hidden / c->heads;
+  if (dh % 8 != 0 || dh > 128) { *why = "head dim must be a multiple of 8 and <= 128"; return false; }
+  if (c->mlp <= 0 || c->mlp % 8 != 0) { *why = "mlp must be a positive multiple of 8"; return false; }
+  if (c->layers_local < 0 || c->layers_global < 0) { *why = "layer counts must be >= 0"; return false; }
+  if (c->has_cls != 0 && c->has_cls != 1) { *why = "has_cls must be 0 or 1"; return false; }
+  if (c->final_ln != 0 && c->final_ln != 1) { *why = "final_ln must be 0 or 1"; return false; }
+  if (!(c->ln_eps >= 0.f) || !std::isfinite(c->ln_eps)) { *why = "ln_eps must be finite and >= 0"; return false; }
+  if (c->proj_layers < 0 || c->proj_layers > 2) { *why = "proj_layers must be 0, 1 or 2"; return false; }
+  for (int i = 0; i < c->proj_layers; ++i)
+    if (c->proj_dims[i] <= 0 || c->proj_dims[i] % 8 != 0) { *why = "proj_dims must be positive multiples of 8"; return false; }
+  if (c->dtype != VIT_DTYPE_FP32 && c->dtype != VIT_DTYPE_BF16) { *why = "dtype must be VIT_DTYPE_FP32 or VIT_DTYPE_BF16"; return false; }
+  if (c->hidden > 4096) { *why = "hidden must be <= 4096"; return false; }
+
+  d->S = c->image_size; d->p = c->patch_size; d->C = c->channels;
+  d->g = d->S / d->p; d->P = d->g * d->g; d->T = d->P + c->has_cls;
+  d->Kp = d->C * d->p * d->p; d->Kp_pad = (int)round_up(d->Kp, 64);
+  d->D = c->hidden; d->H = c->heads; d->dh = dh; d->M = c->mlp;
+  d->dhp = dh <= 64 ? 64 : dh <= 80 ? 80 : dh <= 96 ? 96 : 128;
+  d->Dp = (int)round_up(d->D, 64);
+  d->QKVN = 3 * d->H * d->dhp;
+  d->Op = (int)round_up(d->H * d->dhp, 64);
+  d->Mp = (int)round_up(d->M, 64);
+  d->L_loc = c->layers_local; d->L = c->layers_local + c->layers_global;
+  d->proj_layers = c->proj_layers;
+  d->proj_dims[0] = c->proj_dims[0]; d->proj_dims[1] = c->proj_dims[1];
+  d->proj0_ld = c->proj_layers == 2 ? (int)round_up(c->proj_dims[0], 64) : 0;
+  d->out_dim = c->proj_layers ? c->proj_dims[c->proj_layers - 1] : d->D;
+  d->bf16 = c->dtype == VIT_DTYPE_BF16; d->es = d->bf16 ? 2 : 4;
+  d->eps = c->ln_eps; d->has_cls = c->has_cls; d->final_ln = c->final_ln;
+  return true;
+}
+
+size_t weight_count(const Dims& d) {
+  size_t D = d.D, M = d.M, n = 0;
+  n += D * d.Kp + D + (d.has_cls ? D : 0) + (size_t)d.T * D;
+  n += (size_t)d.L * (2 * D + 3 * D * D + 3 * D + D * D + D + 2 * D + M * D + M + D * M + D);
+  if (d.final_ln) n += 2 * D;
+  size_t in = D;
+  for (int i = 0; i < d.proj_layers; ++i) { n += (size_t)d.proj_dims[i] * in + d.proj_dims[i]; in = d.proj_dims[i]; }
+  return n;
+}
+
+// One matrix product's device-side weights.
+struct Linear {
+  const void* W = nullptr;   // [rows_pad, K] activation element type
+  const float* bias = nullptr;
+  int N = 0;                 // columns written
+  int K = 0;                 // padded contraction length = leading dimension of W
+};
+
+struct Layer {
+  const float *ln1_g, *ln1_b, *ln2_g, *ln2_b;
+  Linear qkv, wo, w1, w2;
+};
+
+// Builds the device image of all weights in host memory, then uploads it in one copy.
+struct Arena {
+  std::vector<unsigned char> host;
+  size_t reserve(size_t bytes) {
+    size_t off = (host.size() + 255) / 256 * 256;
+    host.resize(off + bytes, 0);
+    return off;
+  }
+};
+
+struct StageSlot {
+  void* host = nullptr;
+  size_t cap = 0;
+  hipEvent_t done = nullptr;
+  bool used = false;
+};
+
+struct ProfRec { int family; hipEvent_t start, stop; };
+
+}  // namespace
+
+struct vit_encoder {
+  vit_config_t cfg;
+  Dims d;
+  int device = 0;
+  unsigned char* dev_weights = nullptr;
+  size_t dev_weight_bytes = 0;
+  Linear patch, proj[2];
+  const float *cls = nullptr, *pos = nullptr, *lnf_g = nullptr, *lnf_b = nullptr;
+  std::vector<Layer> layers;
+  StageSlot stage[4];
+  int next_stage = 0;
+  bool profiling = false;
+  std::vector<ProfRec> prof;
+  std::vector<hipEvent_t> free_events;
+  double prof_ms[VIT_PROF_COUNT] = {0, 0, 0, 0};
+  int64_t prof_n[VIT_PROF_COUNT] = {0, 0, 0, 0};
+};
+
+namespace {
+
+// Copies src[rows, cols] (fp32, row-major) into the arena as [rows_pad, ld] of the activation
+// element type, mapping source (row, col) through row_map / col_map (nullptr = identity).
+size_t put_matrix(Arena& ar, const Dims& d, const float* src, int rows, int cols, int rows_pad, int ld,
+                  const std::vector<int>* row_map, const std::vector<int>* col_map) {
+  const size_t off = ar.reserve((size_t)rows_pad * ld * d.es);
+  for (int r = 0; r < rows; ++r) {
+    const int rr = row_map ? (*row_map)[r] : r;
+    unsigned char* dst = ar.host.data() + off + (size_t)rr * ld * d.es;
+    const float* s = src + (size_t)r * cols;
+    if (d.bf16) {
+      bf16_t* o = (bf16_t*)dst;
+      if (col_map) for (int c = 0; c < cols; ++c) o[(*col_map)[c]] = f32_to_bf16(s[c]);
+      else for (int c = 0; c < cols; ++c) o[c] = f32_to_bf16(s[c]);
+    } else {
+      float* o = (float*)dst;
+      if (col_map) for (int c = 0; c < cols; ++c) o[(*col_map)[c]] = s[c];
+      else memcpy(o, s, (size_t)cols * 4);
+    }
+  }
+  return off;
+}
+
+size_t put_vector(Arena& ar, const float* src, int n, int n_pad, const std::vector<int>* map) {
+  const size_t off = ar.reserve((size_t)n_pad * 4);
+  float* o = (float*)(ar.host.data() + off);
+  for (int i = 0; i < n; ++i) o[map ? (*map)[i] : i] = src[i];
+  return off;
+}
+
+struct PendingLinear { Linear* dst; size_t w_off, b_off; };
+struct PendingPtr { const float** dst; size_t off; };
+
+hipEvent_t get_event(vit_encoder* e) {
+  if (!e->free_events.empty()) {
+    hipEvent_t ev = e->free_events.back();
+    e->free_events.pop_back();
+    return ev;
+  }
+  hipEvent_t ev = nullptr;
+  if (hipEventCreate(&ev) != hipSuccess) return nullptr;
+  return ev;
+}
+
+struct ProfScope {
+  vit_encoder* e;
+  hipStream_t s;
+  int family;
+  hipEvent_t start = nullptr, stop = nullptr;
+  ProfScope(vit_encoder* e_, hipStream_t s_, int family_) : e(e_), s(s_), family(family_) {
+    if (!e->profiling) return;
+    start = get_event(e);
+    stop = get_event(e);
+    if (start && stop) (void)hipEventRecord(start, s);
+  }
+  ~ProfScope() {
+    if (!e->profiling || !start || !stop) return;
+    (void)hipEventRecord(stop, s);
+    e->prof.push_back({family, start, stop});
+  }
+};
+
+}  // namespace
+
+extern "C" {
+
+const char* vit_last_error(void) { return g_err; }
+
+size_t vit_weight_count(const vit_config_t* cfg) {
+  Dims d;
+  const char* why;
+  if (!derive(cfg, &d, &why)) return 0;
+  return weight_count(d);
+}
+
+vit_status_t vit_encoder_create(const vit_config_t* cfg, const float* weights, size_t n_weights, int device,
+                                vit_encoder_t** out) {
+  if (out) *out = nullptr;
+  if (!cfg || !weights || !out) return fail(VIT_EINVAL, "vit_encoder_create: NULL argument");
+  Dims d;
+  const char* why;
+  if (!derive(cfg, &d, &why)) return fail(VIT_EINVAL, "vit_encoder_create: invalid config: %s", why);
+  if (n_weights != weight_count(d))
+    return fail(VIT_EINVAL, "vit_encoder_create: n_weights = %zu but the config needs %zu", n_weights, weight_count(d));
+  int ndev = 0;
+  HIP_TRY(hipGetDeviceCount(&ndev));
+  if (device < 0 || device >= ndev) return fail(VIT_EINVAL, "vit_encoder_create: device %d of %d", device, ndev);
+  HIP_TRY(hipSetDevice(device));
+
+  vit_encoder* e = new (std::nothrow) vit_encoder();
+  if (!e) return fail(VIT_ENOMEM, "vit_encoder_create: out of host memory");
+  e->cfg = *cfg;
+  e->d = d;
+  e->device = device;
+
+  Arena ar;
+  std::vector<PendingLinear> plin;
+  std::vector<PendingPtr> pptr;
+  try {
+    e->layers.resize(d.L);
+    const float* w = weights;
+    auto take = [&](size_t n) { const float* p = w; w += n; return p; };
+    auto add_linear = [&](Linear* dst, const float* W, const float* b, int rows, int cols, int N, int K,
+                          const std::vector<int>* row_map, const std::vector<int>* col_map) {
+      const int rows_pad = (int)round_up(N, 256);
+      const size_t wo = put_matrix(ar, d, W, rows, cols, rows_pad, K, row_map, col_map);
+      const size_t bo = put_vector(ar, b, rows, rows_pad, row_map);
+      dst->N = N;
+      dst->K = K;
+      plin.push_back({dst, wo, bo});
+    };
+    auto add_vec = [&](const float** dst, const float* v, int n) { pptr.push_back({dst, put_vector(ar, v, n, n, nullptr)}); };
+
+    // head-padded orderings: source row s*D + h*dh + j -> (s*H + h)*dhp + j; source col h*dh + j -> h*dhp + j
+    std::vector<int> qkv_rows(3 * d.D), o_cols(d.D);
+    for (int s = 0; s < 3; ++s)
+      for (int h = 0; h < d.H; ++h)
+        for (int j = 0; j < d.dh; ++j) qkv_rows[s * d.D + h * d.dh + j] = (s * d.H + h) * d.dhp + j;
+    for (int h = 0; h < d.H; ++h)
+      for (int j = 0; j < d.dh; ++j) o_cols[h * d.dh + j] = h * d.dhp + j;
+
+    const float* pw = take((size_t)d.D * d.Kp);
+    const float* pb = take(d.D);
+    add_linear(&e->patch, pw, pb, d.D, d.Kp, d.D, d.Kp_pad, nullptr, nullptr);
+    if (d.has_cls) add_vec(&e->cls, take(d.D), d.D);
+    add_vec(&e->pos, take((size_t)d.T * d.D), d.T * d.D);
+    for (int l = 0; l < d.L; ++l) {
+      Layer& L = e->layers[l];
+      add_vec(&L.ln1_g, take(d.D), d.D);
+      add_vec(&L.ln1_b, take(d.D), d.D);
+      const float* wq = take((size_t)3 * d.D * d.D);
+      const float* bq = take(3 * d.D);
+      add_linear(&L.qkv, wq, bq, 3 * d.D, d.D, d.QKVN, d.Dp, &qkv_rows, nullptr);
+      const float* wo = take((size_t)d.D * d.D);
+      const float* bo = take(d.D);
+      add_linear(&L.wo, wo, bo, d.D, d.D, d.D, d.Op, nullptr, &o_cols);
+      add_vec(&L.ln2_g, take(d.D), d.D);
+      add_vec(&L.ln2_b, take(d.D), d.D);
+      const float* w1 = take((size_t)d.M * d.D);
+      const float* b1 = take(d.M);
+      add_linear(&L.w1, w1, b1, d.M, d.D, d.Mp, d.Dp, nullptr, nullptr);
+      const float* w2 = take((size_t)d.D * d.M);
+      const float* b2 = take(d.D);
+      add_linear(&L.w2, w2, b2, d.D, d.M, d.D, d.Mp, nullptr, nullptr);
+    }
+    if (d.final_ln) {
+      add_vec(&e->lnf_g, take(d.D), d.D);
+      add_vec(&e->lnf_b, take(d.D), d.D);
+    }
+    int in = d.D, in_ld = d.Dp;
+    for (int i = 0; i < d.proj_layers; ++i) {
+      const int dout = d.proj_dims[i];
+      const float* W = take((size_t)dout * in);
+      const float* b = take(dout);
+      const bool last = i == d.proj_layers - 1;
+      add_linear(&e->proj[i], W, b, dout, in, last ? dout : d.proj0_ld, in_ld, nullptr, nullptr);
+      in = dout;
+      in_ld = d.proj0_ld;
+    }
+  } catch (const std::bad_alloc&) {
+    delete e;
+    return fail(VIT_ENOMEM, "vit_encoder_create: out of host memory while laying out weights");
+  }
+
+  e->dev_weight_bytes = ar.host.size();
+  hipError_t he = hipMalloc((void**)&e->dev_weights, e->dev_weight_bytes);
+  if (he != hipSuccess) {
+    delete e;
+    return fail(he == hipErrorOutOfMemory ? VIT_ENOMEM : VIT_EDEVICE, "vit_encoder_create: hipMalloc(%zu): %s",
+                ar.host.size(), hipGetErrorString(he));
+  }
+  he = hipMemcpy(e->dev_weights, ar.host.data(), e->dev_weight_bytes, hipMemcpyHostToDevice);
+  if (he != hipSuccess) {
+    (void)hipFree(e->dev_weights);
+    delete e;
+    return fail(VIT_EDEVICE, "vit_encoder_create: weight upload: %s", hipGetErrorString(he));
+  }
+  for (auto& p : plin) {
+    p.dst->W = e->dev_weights + p.w_off;
+    p.dst->bias = (const float*)(e->dev_weights + p.b_off);
+  }
+  for (auto& p : pptr) *p.dst = (const float*)(e->dev_weights + p.off);
+  *out = e;
+  return VIT_OK;
+}
+
+void vit_encoder_destroy(vit_encoder_t* e) {
+  if (!e) return;
+  (void)hipSetDevice(e->device);
+  for (auto& r : e->prof) { (void)hipEventDestroy(r.start); (void)hipEventDestroy(r.stop); }
+  for (auto ev : e->free_events) (void)hipEventDestroy(ev);
+  for (auto& s : e->stage) {
+    if (s.done) { (void)hipEventSynchronize(s.done); (void)hipEventDestroy(s.done); }
+    if (s.host) (void)hipHostFree(s.host);
+  }
+  if (e->dev_weights) (void)hipFree(e->dev_weights);
+  delete e;
+}
+
+}  // extern "C"
+
+namespace {
+
+// Workspace carving, shared by query and encode.
+struct Workspace {
+  int64_t n_tok, Mpad, patch_rows_pad, max_work;
+  size_t off_x, off_h, off_qkv, off_o, off_u, off_tables, table_bytes, total;
+};
+
+void plan_workspace(const Dims& d, int64_t n_tiles, Workspace* w) {
+  const int64_t pad = gemm_row_pad();
+  w->n_tok = n_tiles * d.T;
+  w->Mpad = round_up(std::max<int64_t>(w->n_tok, 1), pad);
+  w->patch_rows_pad = round_up(std::max<int64_t>(n_tiles * d.P, 1), pad);
+  const int bq = attention_q_block(d.bf16);
+  w->max_work = n_tiles * ((d.T + bq - 1) / bq);
+  size_t off = 0;
+  auto carve = [&](size_t bytes) { size_t o = off; off += (bytes + 255) / 256 * 256; return o; };
+  w->off_x = carve((size_t)w->Mpad * d.D * 4);
+  w->off_h = carve((size_t)w->Mpad * d.Dp * d.es);
+  w->off_qkv = carve((size_t)w->Mpad * d.QKVN * d.es);
+  w->off_o = carve((size_t)w->Mpad * d.Op * d.es);
+  size_t u_elems = (size_t)w->Mpad * std::max(d.Mp, d.proj0_ld);
+  u_elems = std::max(u_elems, (size_t)w->patch_rows_pad * d.Kp_pad);
+  w->off_u = carve(u_elems * d.es);
+  w->table_bytes = (size_t)(d.L > d.L_loc ? 2 : 1) * w->max_work * sizeof(AttnWork);
+  w->off_tables = carve(w->table_bytes);
+  w->total = off;
+}
+
+}  // namespace
+
+extern "C" {
+
+vit_status_t vit_encoder_query(const vit_encoder_t* e, int32_t n_tiles, int32_t n_images, int64_t* n_tokens,
+                               int32_t* out_dim, size_t* out_bytes, size_t* workspace_bytes) {
+  if (!e) return fail(VIT_EINVAL, "vit_encoder_query: NULL encoder");
+  if (n_tiles < 0 || n_images < 0 || n_images > n_tiles || (n_tiles > 0 && n_images == 0))
+    return fail(VIT_EINVAL, "vit_encoder_query: need 0 <= n_images <= n_tiles and n_images >= 1 when n_tiles > 0");
+  if ((int64_t)n_tiles * e->d.T > (int64_t)INT32_MAX - 1024)
+    return fail(VIT_EINVAL, "vit_encoder_query: n_tiles * tokens_per_tile exceeds the 2^31 row limit");
+  Workspace w;
+  plan_workspace(e->d, n_tiles, &w);
+  if (n_tokens) *n_tokens = w.n_tok;
+  if (out_dim) *out_dim = e->d.out_dim;
+  if (out_bytes) *out_bytes = (size_t)w.n_tok * e->d.out_dim * e->d.es;
+  if (workspace_bytes) *workspace_bytes = n_tiles ? w.total : 0;
+  return VIT_OK;
+}
+
+vit_status_t vit_encode_packed(vit_encoder_t* e, const float* pixels, const int32_t* images_per_request,
+                               int32_t n_requests, const int32_t* tile_offsets, void* out_tokens,
+                               size_t out_capacity_bytes, int64_t* request_token_offsets, void* workspace,
+                               size_t workspace_bytes, void* stream) {
+  if (!e) return fail(VIT_EINVAL, "vit_encode_packed: NULL encoder");
+  if (n_requests < 0) return fail(VIT_EINVAL, "vit_encode_packed: n_requests < 0");
+  if (n_requests > 0 && !images_per_request) return fail(VIT_EINVAL, "vit_encode_packed: images_per_request is NULL");
+  if (!tile_offsets) return fail(VIT_EINVAL, "vit_encode_packed: tile_offsets is NULL");
+  const Dims& d = e->d;
+  int64_t n_images = 0;
+  for (int r = 0; r < n_requests; ++r) {
+    if (images_per_request[r] < 0) return fail(VIT_EINVAL, "vit_encode_packed: images_per_request[%d] < 0", r);
+    n_images += images_per_request[r];
+  }
+  if (n_images > INT32_MAX) return fail(VIT_EINVAL, "vit_encode_packed: too many images");
+  if (tile_offsets[0] != 0) return fail(VIT_EINVAL, "vit_encode_packed: tile_offsets[0] must be 0");
+  for (int64_t i = 0; i < n_images; ++i)
+    if (tile_offsets[i + 1] <= tile_offsets[i])
+      return fail(VIT_EINVAL, "vit_encode_packed: image %lld has no tiles (tile_offsets must increase)", (long long)i);
+  const int64_t n_tiles = tile_offsets[n_images];
+  if (n_tiles * d.T > (int64_t)INT32_MAX - 1024) return fail(VIT_EINVAL, "vit_encode_packed: more than 2^31 token rows");
+  if (request_token_offsets) {
+    int64_t img = 0;
+    request_token_offsets[0] = 0;
+    for (int r = 0; r < n_requests; ++r) {
+      img += images_per_request[r];
+      request_token_offsets[r + 1] = (int64_t)tile_offsets[img] * d.T;
+    }
+  }
+  if (n_tiles == 0) return VIT_OK;
+  if (!pixels || !out_tokens || !workspace) return fail(VIT_EINVAL, "vit_encode_packed: NULL device buffer");
+  if (((uintptr_t)workspace & 255) || ((uintptr_t)out_tokens & 15) || ((uintptr_t)pixels & 15))
+    return fail(VIT_EINVAL, "vit_encode_packed: workspace must be 256-byte aligned, pixels and out_tokens 16-byte aligned");
+
+  Workspace w;
+  plan_workspace(d, n_tiles, &w);
+  const size_t out_need = (size_t)w.n_tok * d.out_dim * d.es;
+  if (out_capacity_bytes < out_need)
+    return fail(VIT_ECAPACITY, "vit_encode_packed: out_tokens holds %zu bytes, %zu needed", out_capacity_bytes, out_need);
+  if (workspace_bytes < w.total)
+    return fail(VIT_ECAPACITY, "vit_encode_packed: workspace holds %zu bytes, %zu needed", workspace_bytes, w.total);
+
+  HIP_TRY(hipSetDevice(e->device));
+  hipStream_t s = (hipStream_t)stream;
+  unsigned char* ws = (unsigned char*)workspace;
+  float* x = (float*)(ws + w.off_x);
+  void* h = ws + w.off_h;
+  void* qkv = ws + w.off_qkv;
+  void* o = ws + w.off_o;
+  void* u = ws + w.off_u;
+  AttnWork* tables = (AttnWork*)(ws + w.off_tables);
+  const int n_tok = (int)w.n_tok;
+
+  // ---- segment planning: blocks of query rows per tile (local layers) and per image (global layers)
+  const int bq = attention_q_block(d.bf16);
+  const bool has_global = d.L > d.L_loc;
+  int n_local = 0, n_global = 0;
+  {
+    StageSlot& slot = e->stage[e->next_stage];
+    e->next_stage = (e->next_stage + 1) % 4;
+    if (slot.used) HIP_TRY(hipEventSynchronize(slot.done));
+    if (slot.cap < w.table_bytes) {
+      if (slot.host) HIP_TRY(hipHostFree(slot.host));
+      slot.host = nullptr;
+      slot.cap = 0;
+      HIP_TRY(hipHostMalloc(&slot.host, w.table_bytes, hipHostMallocDefault));
+      slot.cap = w.table_bytes;
+    }
+    if (!slot.done) HIP_TRY(hipEventCreateWithFlags(&slot.done, hipEventDisableTiming));
+    AttnWork* loc = (AttnWork*)slot.host;
+    for (int64_t t = 0; t < n_tiles; ++t)
+      for (int q = 0; q < d.T; q += bq) loc[n_local++] = {(int32_t)(t * d.T + q), (int32_t)(t * d.T), d.T};
+    AttnWork* glob = loc + w.max_work;
+    if (has_global)
+      for (int64_t i = 0; i < n_images; ++i) {
+        const int start = tile_offsets[i] * d.T, len = (tile_offsets[i + 1] - tile_offsets[i]) * d.T;
+        for (int q = 0; q < len; q += bq) glob[n_global++] = {start + q, start, len};
+      }
+    HIP_TRY(hipMemcpyAsync(tables, slot.host, w.table_bytes, hipMemcpyHostToDevice, s));
+    HIP_TRY(hipEventRecord(slot.done, s));
+    slot.used = true;
+  }
+
+  auto gemm = [&](const Linear& lin, const void* A, int lda, int M, int epi, void* out, int ldo, float* resid) -> hipError_t {
+    GemmArgs a;
+    memset(&a, 0, sizeof(a));
+    a.A = A; a.W = lin.W; a.bias = lin.bias; a.out = out; a.resid = resid; a.pos = e->pos;
+    a.M = M; a.N = lin.N; a.K = lin.K; a.lda = lda; a.ldw = lin.K; a.ldo = ldo;
+    a.patches = d.P; a.tokens = d.T; a.cls = d.has_cls; a.epilogue = epi;
+    ProfScope ps(e, s, VIT_PROF_GEMM);
+    return d.bf16 ? launch_gemm_bf16(a, s) : launch_gemm_f32(a, s);
+  };
+  auto layernorm = [&](const float* g_, const float* b_, int normalize, void* out, int ldo, int out_cols) -> hipError_t {
+    ProfScope ps(e, s, VIT_PROF_LAYERNORM);
+    return launch_layernorm(x, d.D, out, ldo, out_cols, g_, b_, d.eps, n_tok, d.D, normalize, d.bf16, s);
+  };
+
+  // ---- patch embedding: gather -> matrix product with (+bias, +pos, row remap) epilogue; CLS rows
+  {
+    ProfScope ps(e, s, VIT_PROF_PATCHIFY);
+    HIP_TRY(launch_patch_gather(pixels, u, d.Kp_pad, (int)n_tiles, d.C, d.S, d.p, d.g, d.Kp_pad, d.bf16, s));
+    if (d.has_cls) HIP_TRY(launch_cls_rows(x, d.D, e->cls, e->pos, (int)n_tiles, d.T, d.D, s));
+  }
+  HIP_TRY(gemm(e->patch, u, d.Kp_pad, (int)(n_tiles * d.P), EPI_PATCH, nullptr, d.D, x));
+  if (d.Op > d.H * d.dhp) HIP_TRY(launch_fill_zero_cols(o, d.Op, n_tok, d.H * d.dhp, d.Op, d.es, s));
+
+  // ---- transformer blocks
+  for (int l = 0; l < d.L; ++l) {
+    const Layer& L = e->layers[l];
+    HIP_TRY(layernorm(L.ln1_g, L.ln1_b, 1, h, d.Dp, d.Dp));
+    HIP_TRY(gemm(L.qkv, h, d.Dp, n_tok, EPI_BIAS, qkv, d.QKVN, nullptr));
+    {
+      const bool global = l >= d.L_loc;
+      AttnArgs a;
+      a.qkv = qkv; a.out = o;
+      a.work = global ? tables + w.max_work : tables;
+      a.n_work = global ? n_global : n_local;
+      a.heads = d.H; a.dh = d.dh; a.dh_pad = d.dhp; a.ld_qkv = d.QKVN; a.ld_o = d.Op;
+      ProfScope ps(e, s, VIT_PROF_ATTENTION);
+      HIP_TRY(d.bf16 ? launch_attention_bf16(a, s) : launch_attention_f32(a, s));
+    }
+    HIP_TRY(gemm(L.wo, o, d.Op, n_tok, EPI_BIAS_RESIDUAL, nullptr, d.D, x));
+    HIP_TRY(layernorm(L.ln2_g, L.ln2_b, 1, h, d.Dp, d.Dp));
+    HIP_TRY(gemm(L.w1, h, d.Dp, n_tok, EPI_BIAS_GELU, u, d.Mp, nullptr));
+    HIP_TRY(gemm(L.w2, u, d.Mp, n_tok, EPI_BIAS_RESIDUAL, nullptr, d.D, x));
+  }
+
+  // ---- final LayerNorm and projector
+  if (d.proj_layers == 0) {
+    HIP_TRY(layernorm(e->lnf_g, e->lnf_b, d.final_ln, out_tokens, d.D, d.D));
+  } else {
+    HIP_TRY(layernorm(e->lnf_g, e->lnf_b, d.final_ln, h, d.Dp, d.Dp));
+    if (d.proj_layers == 1) {
+      HIP_TRY(gemm(e->proj[0], h, d.Dp, n_tok, EPI_BIAS, out_tokens, d.out_dim, nullptr));
+    } else {
+      HIP_TRY(gemm(e->proj[0], h, d.Dp, n_tok, EPI_BIAS_GELU, u, d.proj0_ld, nullptr));
+      HIP_TRY(gemm(e->proj[1], u, d.proj0_ld, n_tok, EPI_BIAS, out_tokens, d.out_dim, nullptr));
+    }
+  }
+  return VIT_OK;
+}
+
+vit_status_t vit_profile_enable(vit_encoder_t* e, int enable) {
+  if (!e) return fail(VIT_EINVAL, "vit_profile_enable: NULL encoder");
+  HIP_TRY(hipSetDevice(e->device));
+  for (auto& r : e->prof) {
+    HIP_TRY(hipEventSynchronize(r.stop));
+    e->free_events.push_back(r.start);
+    e->free_events.push_back(r.stop);
+  }
+  e->prof.clear();
+  for (int i = 0; i < VIT_PROF_COUNT; ++i) { e->prof_ms[i] = 0; e->prof_n[i] = 0; }
+  e->profiling = enable != 0;
+  return VIT_OK;
+}
+
+vit_status_t vit_profile_read(vit_encoder_t* e, double* ms, int64_t* launches) {
+  if (!e || !ms || !launches) return fail(VIT_EINVAL, "vit_profile_read: NULL argument");
+  HIP_TRY(hipSetDevice(e->device));
+  for (auto& r : e->prof) {
+    HIP_TRY(hipEventSynchronize(r.stop));
+    float t = 0.f;
+    HIP_TRY(hipEventElapsedTime(&t, r.start, r.stop));
+    e->prof_ms[r.family] += t;
+    e->prof_n[r.family] += 1;
+    e->free_events.push_back(r.start);
+    e->free_events.push_back(r.stop);
+  }
+  e->prof.clear();
+  for (int i = 0; i < VIT_PROF_COUNT; ++i) { ms[i] = e->prof_ms[i]; launches[i] = e->prof_n[i]; }
+  return VIT_OK;
+}
+
+}  // extern "C"

@@ -1,0 +1,146 @@
+"""GPU parity: the HIP library through its C ABI against the CPU oracle, on seeded inputs."""
+import numpy as np
+import pytest
+
+import gen
+from parity_util import assert_parity, check_case, gpu_encode, say
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.mark.parametrize("name,tpi,ipr", [
+    ("test_small_fp32", [1, 3, 2], [1, 0, 2]),
+    ("test_small_bf16", [1, 3, 2], [1, 0, 2]),
+    ("test_dh72_bf16", [2, 1, 1], [3]),
+    ("test_dh80_bf16", [3, 1], [1, 1]),
+    ("test_medium_fp32", [2, 1], [2]),
+    ("test_medium_bf16", [2, 1, 4], [1, 1, 1]),
+])
+def test_small_configs_match_oracle(name, tpi, ipr):
+    say(f"case {name} tiles_per_image={tpi} images_per_request={ipr}")
+    check_case(gen.get_config(name), tpi, ipr, label=name)
+
+
+@pytest.mark.parametrize("name", ["test_medium_bf16", "test_dh80_bf16", "test_medium_fp32"])
+def test_large_weights_sharpen_attention(name):
+    """Weights x4 push softmax away from uniform and GELU away from linear."""
+    say(f"case {name} weights x4")
+    check_case(gen.get_config(name), [2, 3], [2], wscale=4.0, label=name + " x4")
+
+
+def test_ragged_many_tiles_bf16():
+    """Enough rows for several 256-row GEMM tiles plus a ragged tail; heavy-tailed request sizes."""
+    cfg = gen.get_config("test_medium_bf16")          # 226 tokens per tile
+    tpi = [1, 5, 1, 1, 2, 7, 1, 3]                     # 21 tiles -> 4746 rows
+    say("case ragged 21 tiles")
+    check_case(cfg, tpi, [1, 0, 4, 3], label="ragged")
+
+
+def test_packing_invariance_on_gpu():
+    """Reordering images / re-splitting requests must not change an image's tokens (beyond parity)."""
+    cfg = gen.get_config("test_medium_bf16")
+    weights = gen.make_weights(cfg, seed=0)
+    tpi = [2, 1, 3]
+    to = np.concatenate([[0], np.cumsum(tpi)]).astype(np.int32)
+    px = gen.make_pixels(cfg, 6, seed=1)
+    T = gen.tokens_per_tile(cfg)
+    say("case packing invariance")
+    a, rto_a = gpu_encode(cfg, weights, px, [3], to)
+    b, rto_b = gpu_encode(cfg, weights, px, [1, 1, 1], to)
+    assert np.array_equal(a, b)
+    assert list(rto_a) == [0, 6 * T] and list(rto_b) == [0, 2 * T, 3 * T, 6 * T]
+    perm = [2, 0, 1]
+    tiles = [list(range(to[i], to[i + 1])) for i in range(3)]
+    px_p = np.concatenate([px[tiles[i]] for i in perm])
+    to_p = np.concatenate([[0], np.cumsum([tpi[i] for i in perm])]).astype(np.int32)
+    c, _ = gpu_encode(cfg, weights, px_p, [2, 1], to_p)
+    bitwise = True
+    for j, i in enumerate(perm):
+        ca, aa = c[to_p[j] * T:to_p[j + 1] * T], a[to[i] * T:to[i + 1] * T]
+        bitwise &= bool(np.array_equal(ca, aa))
+        assert_parity(ca, aa, "bf16", f"permuted image {i}")
+    say(f"    bitwise invariant under image permutation: {bitwise}")
+
+
+def test_empty_and_text_only_requests():
+    import torch
+
+    import paper_2502_00937_amd as V
+
+    cfg = gen.get_config("test_small_bf16")
+    enc = V.VitEncoder(cfg, gen.make_weights(cfg))
+    px = torch.zeros((0, 3, cfg["image_size"], cfg["image_size"]), device="cuda")
+    out, rto = enc.encode(px, [0, 0], [0])
+    assert out.shape[0] == 0 and list(rto) == [0, 0, 0]
+    out, rto = enc.encode(px, [], [0])
+    assert out.shape[0] == 0 and list(rto) == [0]
+    enc.close()
+
+
+def test_error_paths_launch_nothing():
+    import torch
+
+    import paper_2502_00937_amd as V
+    from paper_2502_00937_amd import binding as B
+
+    cfg = gen.get_config("test_small_bf16")
+    enc = V.VitEncoder(cfg, gen.make_weights(cfg))
+    S = cfg["image_size"]
+    px = torch.zeros((2, 3, S, S), device="cuda")
+    n_tok, out_dim, out_bytes, ws_bytes = enc.query(2, 2)
+    out = torch.full((n_tok, out_dim), 7.0, dtype=torch.bfloat16, device="cuda")
+    ws = torch.empty(ws_bytes, dtype=torch.uint8, device="cuda")
+    with pytest.raises(V.VitError) as ei:      # output too small
+        V.vit_encode_packed(enc.handle, px.data_ptr(), [2], [0, 1, 2], out.data_ptr(), out_bytes - 2, ws.data_ptr(),
+                            ws_bytes)
+    assert ei.value.status == B.VIT_ECAPACITY
+    with pytest.raises(V.VitError) as ei:      # workspace too small
+        V.vit_encode_packed(enc.handle, px.data_ptr(), [2], [0, 1, 2], out.data_ptr(), out_bytes, ws.data_ptr(),
+                            ws_bytes - 256)
+    assert ei.value.status == B.VIT_ECAPACITY
+    with pytest.raises(V.VitError) as ei:      # image without tiles
+        V.vit_encode_packed(enc.handle, px.data_ptr(), [2], [0, 2, 2], out.data_ptr(), out_bytes, ws.data_ptr(),
+                            ws_bytes)
+    assert ei.value.status == B.VIT_EINVAL
+    with pytest.raises(V.VitError) as ei:      # negative image count
+        V.vit_encode_packed(enc.handle, px.data_ptr(), [-1], [0], out.data_ptr(), out_bytes, ws.data_ptr(), ws_bytes)
+    assert ei.value.status == B.VIT_EINVAL
+    torch.cuda.synchronize()
+    assert bool((out == 7.0).all())
+    enc.close()
+
+
+def test_repeated_launches_are_deterministic():
+    import torch
+
+    import paper_2502_00937_amd as V
+
+    cfg = gen.get_config("test_medium_bf16")
+    enc = V.VitEncoder(cfg, gen.make_weights(cfg))
+    px = torch.from_numpy(gen.make_pixels(cfg, 5)).cuda()
+    outs = []
+    for _ in range(6):                     # more launches than staging slots
+        out, _ = enc.encode(px, [2, 1], [0, 2, 3, 5])
+        outs.append(out.clone())
+    torch.cuda.synchronize()
+    for o in outs[1:]:
+        assert torch.equal(o, outs[0])
+    enc.close()
+
+
+def test_profile_counters():
+    import torch
+
+    import paper_2502_00937_amd as V
+
+    cfg = gen.get_config("test_small_bf16")
+    enc = V.VitEncoder(cfg, gen.make_weights(cfg))
+    px = torch.from_numpy(gen.make_pixels(cfg, 2)).cuda()
+    enc.profile_enable(True)
+    enc.encode(px, [2], [0, 1, 2])
+    prof = enc.profile_read()
+    L = cfg["layers_local"] + cfg["layers_global"]
+    assert prof["gemm"][1] == 1 + 4 * L + 2 and prof["attention"][1] == L and prof["layernorm"][1] == 2 * L + 1
+    assert all(v[0] > 0 for v in prof.values())
+    enc.profile_enable(False)
+    enc.close()

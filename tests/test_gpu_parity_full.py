@@ -1,0 +1,58 @@
+"""GPU parity at the benchmark's full sizes, in the launch configuration bench.py times.
+
+The GPU encodes the whole batch; the oracle encodes whole images sampled from it (an image's
+tokens depend on its own tiles only), because the full batches are 100+ TFLOP.
+"""
+import numpy as np
+import pytest
+
+import gen
+from parity_util import check_case, say
+
+pytestmark = pytest.mark.gpu
+
+
+def _workload(name):
+    cfg, ipr, to = gen.make_workload(name)
+    return cfg, list(ipr), list(np.diff(to))
+
+
+def test_cfg1_tiny_fp32_full():
+    cfg, ipr, tpi = _workload("cfg1")
+    say("case cfg1 (4 images, fp32)")
+    got, _ = check_case(cfg, tpi, ipr, label="cfg1")
+    assert got.shape == (4 * 197, 192)
+
+
+def test_cfg2_vitl14_336_full():
+    cfg, ipr, tpi = _workload("cfg2")
+    say("case cfg2 (8 images)")
+    got, _ = check_case(cfg, tpi, ipr, label="cfg2")
+    assert got.shape == (8 * 577, 4096)
+
+
+def test_cfg3_ragged_batch_sampled():
+    cfg, ipr, tpi = _workload("cfg3")
+    # first, last, one inside the 32-image request (request 47), one single-image request
+    first_of_req = np.concatenate([[0], np.cumsum(ipr)])
+    images = [0, int(first_of_req[47]) + 17, int(first_of_req[60]), 259]
+    say(f"case cfg3 (260 images / 64 requests), oracle on images {images}")
+    got, _ = check_case(cfg, tpi, ipr, images=images, label="cfg3")
+    assert got.shape == (260 * 577, 4096)
+
+
+def test_cfg4_siglip_tiles_sampled():
+    cfg, ipr, tpi = _workload("cfg4")
+    images = [5, 127]          # a 2-tile image and the last image (5 tiles)
+    assert tpi[5] == 2
+    say(f"case cfg4 (128 images / 591 tiles), oracle on images {images}")
+    got, _ = check_case(cfg, tpi, ipr, images=images, oracle_dtype=np.float32, label="cfg4")
+    assert got.shape == (591 * 729, 4096)
+
+
+def test_cfg5_local_global_sampled():
+    cfg, ipr, tpi = _workload("cfg5")
+    images = [31]
+    say(f"case cfg5 (32 images x 4 tiles), oracle on image {images}")
+    got, _ = check_case(cfg, tpi, ipr, images=images, oracle_dtype=np.float32, label="cfg5")
+    assert got.shape == (128 * 1601, 1280)

@@ -1,0 +1,89 @@
+"""Host-only checks of the C-ABI library: it loads, exports what the header declares, and its
+pure-host entry points behave.  No kernel is launched."""
+import os
+import re
+
+import numpy as np
+import pytest
+
+import gen
+import paper_2502_00937_amd as V
+from paper_2502_00937_amd import binding as B
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def declared_symbols():
+    text = open(os.path.join(ROOT, "include", "vitenc.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(vit_[a-z_]+)\s*\(", text)))
+
+
+def test_library_loads_and_exports_every_declared_symbol():
+    lib = V.load_library()
+    names = declared_symbols()
+    assert {"vit_encoder_create", "vit_encode_packed", "vit_encoder_destroy", "vit_encoder_query",
+            "vit_weight_count", "vit_last_error", "vit_profile_enable", "vit_profile_read"} <= set(names)
+    for n in names:
+        assert hasattr(lib, n), n
+
+
+def test_struct_matches_header_field_order():
+    text = open(os.path.join(ROOT, "include", "vitenc.h")).read()
+    body = text[text.index("typedef struct {"):text.index("} vit_config_t;")]
+    body = re.sub(r"/\*.*?\*/", "", body, flags=re.S)
+    fields = re.findall(r"(?:int32_t|float)\s+([a-z_]+)(?:\[\d\])?;", body)
+    assert fields == [f[0] for f in B.vit_config_t._fields_]
+
+
+def test_weight_count_matches_generator_for_all_presets():
+    for name in gen.CONFIGS:
+        cfg = gen.get_config(name)
+        assert V.vit_weight_count(cfg) == gen.weight_count(cfg), name
+
+
+def test_weight_count_rejects_bad_configs():
+    base = gen.get_config("test_small_bf16")
+    for key, val in [("heads", 3), ("hidden", 0), ("patch_size", 0), ("proj_layers", 3), ("mlp", 7),
+                     ("hidden", 20), ("has_cls", 2), ("layers_local", -1), ("ln_eps", float("nan"))]:
+        cfg = dict(base)
+        cfg[key] = val
+        if key == "proj_layers":
+            cfg["proj_dims"] = (8, 8)
+        assert V.vit_weight_count(cfg) == 0, (key, val)
+
+
+def test_create_rejects_null_and_bad_arguments_without_a_device():
+    lib = V.load_library()
+    import ctypes as C
+
+    handle = C.c_void_p(123)
+    st = lib.vit_encoder_create(None, None, 0, 0, C.byref(handle))
+    assert st == B.VIT_EINVAL and handle.value is None
+    assert b"NULL" in lib.vit_last_error()
+    cfg = B._to_struct(gen.get_config("test_small_bf16"))
+    w = np.zeros(4, dtype=np.float32)
+    st = lib.vit_encoder_create(C.byref(cfg), w.ctypes.data, w.size, 0, C.byref(handle))
+    assert st == B.VIT_EINVAL and b"n_weights" in lib.vit_last_error()
+    assert lib.vit_encoder_query(None, 1, 1, None, None, None, None) == B.VIT_EINVAL
+    assert lib.vit_encode_packed(None, None, None, 0, None, None, 0, None, None, 0, None) == B.VIT_EINVAL
+    lib.vit_encoder_destroy(None)  # NULL-safe
+
+
+def test_no_cpu_fallback():
+    import torch
+
+    if torch.cuda.is_available():
+        pytest.skip("GPU present")
+    cfg = gen.get_config("test_small_bf16")
+    with pytest.raises(RuntimeError):
+        V.VitEncoder(cfg, gen.make_weights(cfg))
+
+
+def test_product_does_not_import_oracle():
+    pkg = os.path.join(ROOT, "paper_2502_00937_amd")
+    for dirpath, _, files in os.walk(pkg):
+        for f in files:
+            if f.endswith((".py", ".hip", ".h", ".cpp")):
+                src = open(os.path.join(dirpath, f)).read()
+                assert "oracle" not in src.lower(), os.path.join(dirpath, f)
