@@ -1,0 +1,158 @@
+#!/usr/bin/env python3
+"""Benchmark: one packed encode of the ViT-L/14-336 ragged multi-request batch per step.
+
+Prints ONE JSON line.  A step is one vit_encode_packed call over the whole batch
+(64 requests, 260 images, 150 020 tokens) with pixels already resident in HBM.
+`roofline` is for the dominant kernel family (the bf16 MFMA matrix products), timed with
+HIP events on the launch stream inside the timed region; `cpu_baseline` times the CPU
+oracle on a bounded sample of whole images from the same batch.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+import numpy as np  # noqa: E402
+
+PEAK_BF16_TFLOPS = 2500.0  # MI355X dense bf16 MFMA peak
+HBM_PEAK_GBS = 8000.0
+
+
+def flops(cfg, tile_offsets):
+    """Algorithmic FLOPs (2 per multiply-add; LN/softmax/GELU/bias excluded). Returns (total, gemm, attention)."""
+    g = cfg["image_size"] // cfg["patch_size"]
+    P = g * g
+    T = P + cfg["has_cls"]
+    K = cfg["channels"] * cfg["patch_size"] ** 2
+    D, M = cfg["hidden"], cfg["mlp"]
+    L_loc, L_glob = cfg["layers_local"], cfg["layers_global"]
+    tpi = np.diff(np.asarray(tile_offsets, dtype=np.int64))
+    n_tiles = int(tpi.sum())
+    gemm = n_tiles * (2.0 * P * K * D + (L_loc + L_glob) * (2.0 * T * D * 3 * D + 2.0 * T * D * D + 4.0 * T * D * M))
+    d_in = D
+    for i in range(cfg["proj_layers"]):
+        gemm += n_tiles * 2.0 * T * d_in * cfg["proj_dims"][i]
+        d_in = cfg["proj_dims"][i]
+    attn = n_tiles * L_loc * 4.0 * T * T * D + float(sum(L_glob * 4.0 * (n * T) * (n * T) * D for n in tpi))
+    return gemm + attn, gemm, attn
+
+
+def cpu_baseline(cfg, weights, px, tile_offsets, n_sample):
+    """Oracle (fp32, as it stands) on the first n_sample images of the batch; returns the JSON object."""
+    from threadpoolctl import threadpool_info
+
+    from oracle import vit_oracle as O
+
+    w = O.unpack_weights(cfg, weights, np.float32)
+    to = np.asarray(tile_offsets[:n_sample + 1])
+    t0 = time.perf_counter()
+    O.vit_oracle_encode(cfg, w, px[:int(to[-1])], [n_sample], to, dtype=np.float32)
+    dt = time.perf_counter() - t0
+    threads = max([p.get("num_threads", 1) for p in threadpool_info()] + [1])
+    return {
+        "value": n_sample / dt, "unit": "images/s", "cores": int(threads), "kind": "oracle",
+        "sample": f"first {n_sample} images of the batch, fp32 numpy oracle, {dt:.2f} s wall",
+    }
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=10)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--workload", default="cfg3", choices=["cfg1", "cfg2", "cfg3", "cfg4", "cfg5"])
+    ap.add_argument("--cpu-sample", type=int, default=4, help="images the CPU oracle encodes (0 = skip)")
+    ap.add_argument("--no-kernel-events", action="store_true", help="time the steps without per-kernel events")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU (no sharding, no collectives); --gpus must be 1", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+
+    import gen
+    import paper_2502_00937_amd as V
+
+    if not torch.cuda.is_available():
+        print("bench.py: no HIP device visible; there is no CPU path", file=sys.stderr)
+        sys.exit(2)
+    cfg, ipr, to = gen.make_workload(args.workload)
+    n_images, n_tiles = int(ipr.sum()), int(to[-1])
+    T = gen.tokens_per_tile(cfg)
+    weights = gen.make_weights(cfg, seed=0)
+    px = gen.make_pixels(cfg, n_tiles, seed=1)
+    enc = V.VitEncoder(cfg, weights, device=0)
+    px_dev = torch.from_numpy(px).cuda()
+    n_tok, out_dim, _, _ = enc.query(n_tiles, n_images)
+    out = torch.empty((n_tok, out_dim), dtype=torch.bfloat16 if cfg["dtype"] == "bf16" else torch.float32,
+                      device="cuda")
+
+    for _ in range(args.warmup):
+        enc.encode(px_dev, ipr, to, out=out)
+    torch.cuda.synchronize()
+    if not args.no_kernel_events:
+        enc.profile_enable(True)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        enc.encode(px_dev, ipr, to, out=out)
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    ms_per_step = dt / args.steps * 1e3
+
+    total_f, gemm_f, attn_f = flops(cfg, to)
+    result = {
+        "metric": "images/sec + encoder tokens/sec (ViT-L/14-336 ragged batch); % bf16 MFMA peak",
+        "value": n_images / (ms_per_step * 1e-3),
+        "unit": "images/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": cfg["dtype"], "data": "synthetic",
+        "config": {
+            "workload": {"cfg1": "tiny ViT fp32, 4 images", "cfg2": "ViT-L/14-336 + projector, 8 images",
+                         "cfg3": "ViT-L/14-336 + 2-layer projector, ragged batch: 64 requests / 260 images, one launch",
+                         "cfg4": "SigLIP-style 384px, 128 images / 591 tiles",
+                         "cfg5": "ViT-H/14-560, 32 images x 4 tiles, 32 local + 8 global layers"}[args.workload],
+            "requests": int(len(ipr)), "images": n_images, "tiles": n_tiles, "tokens": int(n_tok),
+            "weights": "seeded N(0, 0.02), bf16-rounded", "pixels": "seeded U[-1,1), resident in HBM",
+        },
+        "tokens_per_s": n_tok / (ms_per_step * 1e-3),
+        "tiles_per_s": n_tiles / (ms_per_step * 1e-3),
+        "tflops": total_f / (ms_per_step * 1e-3) / 1e12,
+        "pct_bf16_peak": 100.0 * total_f / (ms_per_step * 1e-3) / 1e12 / PEAK_BF16_TFLOPS,
+    }
+    if not args.no_kernel_events:
+        prof = enc.profile_read()
+        enc.profile_enable(False)
+        fam_ms = {k: v[0] / args.steps for k, v in prof.items()}
+        gemm_ms, gemm_n = prof["gemm"][0] / args.steps, prof["gemm"][1] // args.steps
+        achieved = gemm_f / (gemm_ms * 1e-3) / 1e12
+        result["roofline"] = {
+            "bound": "mfma", "kernel": "gemm_bf16_kernel (all matrix products of one step)",
+            "achieved": achieved, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": achieved / PEAK_BF16_TFLOPS,
+            "traffic": None, "launches_per_step": int(gemm_n), "ms_per_step": gemm_ms,
+            "avg_launch_ms": gemm_ms / max(gemm_n, 1), "flop_per_step": gemm_f,
+        }
+        result["kernel_ms_per_step"] = fam_ms
+        att_ms = fam_ms["attention"]
+        result["attention_tflops"] = attn_f / (att_ms * 1e-3) / 1e12 if att_ms > 0 else None
+        # LayerNorm passes: each reads fp32 [tokens, D] and writes the operand type
+        es = 2 if cfg["dtype"] == "bf16" else 4
+        ln_n = prof["layernorm"][1] // args.steps
+        ln_bytes = ln_n * n_tok * cfg["hidden"] * (4 + es)
+        result["layernorm_gbs"] = ln_bytes / (fam_ms["layernorm"] * 1e-3) / 1e9 if fam_ms["layernorm"] > 0 else None
+    enc.close()
+    if args.cpu_sample > 0:
+        result["cpu_baseline"] = cpu_baseline(cfg, weights, px, to, min(args.cpu_sample, n_images))
+    print(json.dumps(result))
+
+
+if __name__ == "__main__":
+    main()

@@ -1,5 +1,4 @@
 """Helpers shared by the GPU parity tests: run the HIP library and the oracle on the same seeded inputs."""
-import sys
 import time
 
 import numpy as np
@@ -15,8 +14,9 @@ FP32_REL, FP32_COS = 2e-4, 0.999999
 
 
 def say(msg):
-    sys.__stdout__.write(msg + "\n")
-    sys.__stdout__.flush()
+    import conftest
+
+    conftest.progress(msg)
 
 
 def token_metrics(got: np.ndarray, want: np.ndarray):
