@@ -15,13 +15,21 @@ typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
 
 typedef uint16_t bf16_t;  // storage type of a bfloat16 value in global memory
 
-// fp32 -> bf16, round to nearest even (finite inputs; NaN stays NaN).
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+typedef float f32x2 __attribute__((ext_vector_type(2)));
+
+// fp32 -> bf16, round to nearest even; NaN stays NaN.  On the device this is the hardware
+// conversion (v_cvt_pk_bf16_f32), on the host the integer form of the same rounding.
 __host__ __device__ inline bf16_t f32_to_bf16(float f) {
+#if defined(__HIP_DEVICE_COMPILE__)
+  return __builtin_bit_cast(bf16_t, (__bf16)f);
+#else
   union { float f; uint32_t u; } v;
   v.f = f;
   if ((v.u & 0x7FFFFFFFu) > 0x7F800000u) return (bf16_t)((v.u >> 16) | 0x40u);
   v.u += 0x7FFFu + ((v.u >> 16) & 1u);
   return (bf16_t)(v.u >> 16);
+#endif
 }
 __host__ __device__ inline float bf16_to_f32(bf16_t h) {
   union { float f; uint32_t u; } v;
@@ -30,7 +38,8 @@ __host__ __device__ inline float bf16_to_f32(bf16_t h) {
 }
 // two fp32 -> packed pair of bf16 (low half = a)
 __device__ inline uint32_t pack_bf16x2(float a, float b) {
-  return (uint32_t)f32_to_bf16(a) | ((uint32_t)f32_to_bf16(b) << 16);
+  const f32x2 v = {a, b};
+  return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, bf16x2));
 }
 
 // Element-type traits for the two arithmetic modes.

@@ -17,6 +17,8 @@
 // * Workgroup ids are dealt round-robin to the 8 XCDs; each XCD walks its own range of
 //   row blocks in 8 x 4 tile groups so the tiles in flight on one XCD share A and W
 //   slices in that XCD's L2.
+#include <type_traits>
+
 #include "common.h"
 
 namespace vitenc {
@@ -48,6 +50,106 @@ __device__ __forceinline__ void tile_store(const u32x4 (&r)[LOADS], unsigned cha
   }
 }
 
+// Epilogue of one wave.  acc[i][j] is a transposed 32x32 block: the lane holds token row
+// row0 + 32i + (lane & 31); register 4jj + e holds output column ncol0 + 32j + 8jj + 4(lane >> 5) + e.
+// `smem` is free LDS (all waves are past their last tile read); each wave stages its own rows.
+template <int EPI, int FM, int FN>
+__device__ __forceinline__ void wave_epilogue(const GemmArgs& a, f32x16 (&acc)[FM][FN], unsigned char* smem, int row0,
+                                              int ncol0, int wave, int lane) {
+  constexpr int TN = FN * 32;
+  constexpr int STAGE_BF16 = TN * 2 + 16, STAGE_F32 = TN * 4 + 16;  // bytes per staged row (padded)
+  const int lrow = lane & 31, lk = lane >> 5;
+  f32x4 bias[FN][4];
+#pragma unroll
+  for (int j = 0; j < FN; ++j)
+#pragma unroll
+    for (int jj = 0; jj < 4; ++jj) bias[j][jj] = *(const f32x4*)(a.bias + ncol0 + j * 32 + jj * 8 + lk * 4);
+
+  if constexpr (EPI == EPI_PATCH) {
+    // rows are (tile, patch); the residual stream row is tile*T + cls + patch and the position row is added
+#pragma unroll
+    for (int i = 0; i < FM; ++i) {
+      const int row = row0 + i * 32 + lrow;
+      if (row >= a.M) continue;
+      const int tile = row / a.patches, tok = a.cls + (row - tile * a.patches);
+      float* xr = a.resid + ((size_t)tile * a.tokens + tok) * a.ldo;
+      const float* pr = a.pos + (size_t)tok * a.ldo;
+#pragma unroll
+      for (int j = 0; j < FN; ++j)
+#pragma unroll
+        for (int jj = 0; jj < 4; ++jj) {
+          const int col = ncol0 + j * 32 + jj * 8 + lk * 4;
+          if (col < a.N) {
+            const f32x4 p = *(const f32x4*)(pr + col);
+            f32x4 v;
+#pragma unroll
+            for (int e = 0; e < 4; ++e) v[e] = acc[i][j][jj * 4 + e] + bias[j][jj][e] + p[e];
+            *(f32x4*)(xr + col) = v;
+          }
+        }
+    }
+  } else if constexpr (EPI == EPI_BIAS_RESIDUAL) {
+    unsigned char* st = smem + wave * 32 * STAGE_F32;  // this wave's private staging rows
+    constexpr int LPR = TN / 4;                        // lanes per staged row (16 bytes each)
+    constexpr int RPI = 64 / LPR;                      // rows per pass
+#pragma unroll
+    for (int i = 0; i < FM; ++i) {
+#pragma unroll
+      for (int j = 0; j < FN; ++j)
+#pragma unroll
+        for (int jj = 0; jj < 4; ++jj) {
+          f32x4 v;
+#pragma unroll
+          for (int e = 0; e < 4; ++e) v[e] = acc[i][j][jj * 4 + e] + bias[j][jj][e];
+          *(f32x4*)(st + lrow * STAGE_F32 + (j * 32 + jj * 8 + lk * 4) * 4) = v;
+        }
+      __builtin_amdgcn_wave_barrier();
+#pragma unroll
+      for (int p = 0; p < 32 / RPI; ++p) {
+        const int sr = p * RPI + lane / LPR, sc = (lane % LPR) * 4;
+        const int row = row0 + i * 32 + sr, col = ncol0 + sc;
+        const f32x4 v = *(const f32x4*)(st + sr * STAGE_F32 + sc * 4);
+        if (row < a.M && col < a.N) {
+          float* xp = a.resid + (size_t)row * a.ldo + col;
+          f32x4 x = *(const f32x4*)xp;
+          x += v;
+          *(f32x4*)xp = x;
+        }
+      }
+      __builtin_amdgcn_wave_barrier();
+    }
+  } else {  // EPI_BIAS, EPI_BIAS_GELU: bf16 output
+    unsigned char* st = smem + wave * 32 * STAGE_BF16;
+    constexpr int LPR = TN / 8;  // lanes per staged row (16 bytes = 8 bf16 each)
+    constexpr int RPI = 64 / LPR;
+#pragma unroll
+    for (int i = 0; i < FM; ++i) {
+#pragma unroll
+      for (int j = 0; j < FN; ++j)
+#pragma unroll
+        for (int jj = 0; jj < 4; ++jj) {
+          float v[4];
+#pragma unroll
+          for (int e = 0; e < 4; ++e) {
+            v[e] = acc[i][j][jj * 4 + e] + bias[j][jj][e];
+            if constexpr (EPI == EPI_BIAS_GELU) v[e] = gelu_fast(v[e]);
+          }
+          const u32x2 pk = {pack_bf16x2(v[0], v[1]), pack_bf16x2(v[2], v[3])};
+          *(u32x2*)(st + lrow * STAGE_BF16 + (j * 32 + jj * 8 + lk * 4) * 2) = pk;
+        }
+      __builtin_amdgcn_wave_barrier();
+#pragma unroll
+      for (int p = 0; p < 32 / RPI; ++p) {
+        const int sr = p * RPI + lane / LPR, sc = (lane % LPR) * 8;
+        const int row = row0 + i * 32 + sr, col = ncol0 + sc;
+        const u32x4 v = *(const u32x4*)(st + sr * STAGE_BF16 + sc * 2);
+        if (row < a.M && col < a.N) *(u32x4*)((bf16_t*)a.out + (size_t)row * a.ldo + col) = v;
+      }
+      __builtin_amdgcn_wave_barrier();
+    }
+  }
+}
+
 template <int BM, int BN, int WM, int WN, int EPI>
 __global__ __launch_bounds__(WM* WN * 64) void gemm_bf16_kernel(const GemmArgs a, int tiles_m, int tiles_n,
                                                                int mt_per_xcd, int n_bands) {
@@ -56,8 +158,7 @@ __global__ __launch_bounds__(WM* WN * 64) void gemm_bf16_kernel(const GemmArgs a
   constexpr int FM = TM / 32, FN = TN / 32;  // 32x32 MFMA blocks per wave
   constexpr int A_LOADS = BM * 8 / NT, B_LOADS = BN * 8 / NT;
   static_assert(BM * 8 % NT == 0 && BN * 8 % NT == 0, "tile/threads mismatch");
-  constexpr int STAGE_BF16 = TN * 2 + 16, STAGE_F32 = TN * 4 + 16;  // bytes per staged row (padded)
-  static_assert(WM * WN * 32 * STAGE_F32 <= 2 * (BM + BN) * 128, "epilogue staging must fit in the tile buffers");
+  static_assert(WM * WN * 32 * (TN * 4 + 16) <= 2 * (BM + BN) * 128, "epilogue staging must fit in the tile buffers");
 
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
   unsigned char* sA = smem;                 // 2 stages x BM x 128 B
@@ -125,9 +226,48 @@ __global__ __launch_bounds__(WM* WN * 64) void gemm_bf16_kernel(const GemmArgs a
     __syncthreads();
   }
 
-  // ---- epilogue.  acc[i][j] is the transposed block: lane holds token row
-  // m0 + wm*TM + 32i + lrow; register 4jj + e holds output column n0 + wn*TN + 32j + 8jj + 4lk + e.
-  const int ncol0 = n0 + wn * TN;  // first column of this wave
+  wave_epilogue<EPI, FM, FN>(a, acc, smem, m0 + wm * TM, n0 + wn * TN, wave, lane);
+}
+
+// ---------------------------------------------------------------------------------------------
+// Large-problem kernel: persistent, 256 x 256 tile, eight waves (two per SIMD), 128 x 64 per wave.
+//
+// The memory system, not the matrix cores, sets the pace of this product on gfx950: what a compute
+// unit can pull through its L1 is about 100 GB/s, and a 256 x 256 tile needs half of that at full
+// MFMA rate, a 256 x 128 tile three quarters.  Hence the biggest tile the accumulators allow.
+//
+// * One workgroup per compute unit walks a list of tiles.  Operand tiles go global -> LDS directly
+//   (global_load_lds_dwordx4: each lane supplies its own global address, the wave writes 1 KiB of
+//   consecutive LDS) through a ring of four 32-wide k-stages.  The ring runs three steps ahead of
+//   the multiplication and does not stop at tile boundaries, so the next tile's first stages land
+//   while the current tile finishes and its epilogue runs; no launch gap, no cold prologue per tile.
+// * LDS rows are 64 bytes; the 16-byte chunk index is XORed with (row >> 2) & 3, which the lane
+//   achieves by choosing which global chunk it loads, so any 16 consecutive rows of one logical
+//   chunk fall on 16 distinct 16-byte bank groups of the 64 banks.
+// * The loads of a step are spread between its MFMAs: a wave that issued them back to back would
+//   sit in the memory pipeline's back-pressure while the matrix core runs dry.
+// * Tile order: the tile grid is cut into (8-row-block x 4-column-band) groups of 32 tiles, one per
+//   compute unit of an XCD; consecutive groups along N go to consecutive XCDs, so the XCDs working
+//   at the same time share A rows (first fetch fills the memory-side cache for the others) and the
+//   32 units of one XCD share both operands in its L2.
+// * Epilogue staging has its own 18 KiB of LDS (16 rows x 144 bytes per wave).
+constexpr int D_BM = 256, D_BN = 256, D_BK = 32, D_ST = 4;
+constexpr int D_STAGE_BYTES = (D_BM + D_BN) * D_BK * 2;  // 32 KiB
+constexpr int D_STAGING_ROW = 144, D_STAGING_BYTES = 8 * 16 * D_STAGING_ROW;
+constexpr int D_LDS_BYTES = D_ST * D_STAGE_BYTES + D_STAGING_BYTES;  // 146 KiB of the 160 KiB
+constexpr int D_GROUP_M = 8, D_GROUP_N = 4;
+constexpr int D_LOADS = 4;  // direct-to-LDS instructions per wave and stage (2 for A, 2 for W)
+
+typedef const __attribute__((address_space(1))) void* gptr_t;
+typedef __attribute__((address_space(3))) void* lptr_t;
+
+// Epilogue of one wave of the persistent kernel: same register layout as wave_epilogue, but staged
+// 16 rows at a time through the wave's private 16 x 144-byte LDS rows (`st`).
+template <int EPI>
+__device__ __forceinline__ void wave_epilogue_p(const GemmArgs& a, f32x16 (&acc)[4][2], unsigned char* st, int row0,
+                                                int ncol0, int lane) {
+  constexpr int FM = 4, FN = 2;
+  const int lrow = lane & 31, lk = lane >> 5;
   f32x4 bias[FN][4];
 #pragma unroll
   for (int j = 0; j < FN; ++j)
@@ -135,10 +275,9 @@ __global__ __launch_bounds__(WM* WN * 64) void gemm_bf16_kernel(const GemmArgs a
     for (int jj = 0; jj < 4; ++jj) bias[j][jj] = *(const f32x4*)(a.bias + ncol0 + j * 32 + jj * 8 + lk * 4);
 
   if constexpr (EPI == EPI_PATCH) {
-    // rows are (tile, patch); the residual stream row is tile*T + cls + patch and the position row is added
 #pragma unroll
     for (int i = 0; i < FM; ++i) {
-      const int row = m0 + wm * TM + i * 32 + lrow;
+      const int row = row0 + i * 32 + lrow;
       if (row >= a.M) continue;
       const int tile = row / a.patches, tok = a.cls + (row - tile * a.patches);
       float* xr = a.resid + ((size_t)tile * a.tokens + tok) * a.ldo;
@@ -158,41 +297,43 @@ __global__ __launch_bounds__(WM* WN * 64) void gemm_bf16_kernel(const GemmArgs a
         }
     }
   } else if constexpr (EPI == EPI_BIAS_RESIDUAL) {
-    unsigned char* st = smem + wave * 32 * STAGE_F32;  // this wave's private staging rows
-    constexpr int LPR = TN / 4;                        // lanes per staged row (16 bytes each)
-    constexpr int RPI = 64 / LPR;                      // rows per pass
+    // pieces of 16 rows x 32 fp32 columns (128 bytes + pad per staged row)
 #pragma unroll
-    for (int i = 0; i < FM; ++i) {
+    for (int i = 0; i < FM; ++i)
 #pragma unroll
-      for (int j = 0; j < FN; ++j)
+      for (int j = 0; j < FN; ++j) {
+        f32x4 v[4];
 #pragma unroll
-        for (int jj = 0; jj < 4; ++jj) {
-          f32x4 v;
+        for (int jj = 0; jj < 4; ++jj)
 #pragma unroll
-          for (int e = 0; e < 4; ++e) v[e] = acc[i][j][jj * 4 + e] + bias[j][jj][e];
-          *(f32x4*)(st + lrow * STAGE_F32 + (j * 32 + jj * 8 + lk * 4) * 4) = v;
-        }
-      __builtin_amdgcn_wave_barrier();
+          for (int e = 0; e < 4; ++e) v[jj][e] = acc[i][j][jj * 4 + e] + bias[j][jj][e];
 #pragma unroll
-      for (int p = 0; p < 32 / RPI; ++p) {
-        const int sr = p * RPI + lane / LPR, sc = (lane % LPR) * 4;
-        const int row = m0 + wm * TM + i * 32 + sr, col = ncol0 + sc;
-        const f32x4 v = *(const f32x4*)(st + sr * STAGE_F32 + sc * 4);
-        if (row < a.M && col < a.N) {
-          float* xp = a.resid + (size_t)row * a.ldo + col;
-          f32x4 x = *(const f32x4*)xp;
-          x += v;
-          *(f32x4*)xp = x;
+        for (int half = 0; half < 2; ++half) {
+          if ((lrow >> 4) == half) {
+#pragma unroll
+            for (int jj = 0; jj < 4; ++jj)
+              *(f32x4*)(st + (lrow & 15) * D_STAGING_ROW + (jj * 8 + lk * 4) * 4) = v[jj];
+          }
+          __builtin_amdgcn_wave_barrier();
+#pragma unroll
+          for (int p = 0; p < 2; ++p) {  // 8 lanes per row (16 bytes each), 8 rows per pass
+            const int sr = p * 8 + (lane >> 3), sc = (lane & 7) * 4;
+            const int row = row0 + i * 32 + half * 16 + sr, col = ncol0 + j * 32 + sc;
+            const f32x4 t = *(const f32x4*)(st + sr * D_STAGING_ROW + sc * 4);
+            if (row < a.M && col < a.N) {
+              float* xp = a.resid + (size_t)row * a.ldo + col;
+              f32x4 x = *(const f32x4*)xp;
+              x += t;
+              *(f32x4*)xp = x;
+            }
+          }
+          __builtin_amdgcn_wave_barrier();
         }
       }
-      __builtin_amdgcn_wave_barrier();
-    }
-  } else {  // EPI_BIAS, EPI_BIAS_GELU: bf16 output
-    unsigned char* st = smem + wave * 32 * STAGE_BF16;
-    constexpr int LPR = TN / 8;  // lanes per staged row (16 bytes = 8 bf16 each)
-    constexpr int RPI = 64 / LPR;
+  } else {  // EPI_BIAS, EPI_BIAS_GELU: bf16 output, pieces of 16 rows x 64 columns (128 bytes + pad)
 #pragma unroll
     for (int i = 0; i < FM; ++i) {
+      u32x2 pk[FN][4];  // all lanes convert once; the two half-wave passes below only move data
 #pragma unroll
       for (int j = 0; j < FN; ++j)
 #pragma unroll
@@ -203,20 +344,236 @@ __global__ __launch_bounds__(WM* WN * 64) void gemm_bf16_kernel(const GemmArgs a
             v[e] = acc[i][j][jj * 4 + e] + bias[j][jj][e];
             if constexpr (EPI == EPI_BIAS_GELU) v[e] = gelu_fast(v[e]);
           }
-          const u32x2 pk = {pack_bf16x2(v[0], v[1]), pack_bf16x2(v[2], v[3])};
-          *(u32x2*)(st + lrow * STAGE_BF16 + (j * 32 + jj * 8 + lk * 4) * 2) = pk;
+          pk[j][jj] = u32x2{pack_bf16x2(v[0], v[1]), pack_bf16x2(v[2], v[3])};
         }
-      __builtin_amdgcn_wave_barrier();
 #pragma unroll
-      for (int p = 0; p < 32 / RPI; ++p) {
-        const int sr = p * RPI + lane / LPR, sc = (lane % LPR) * 8;
-        const int row = m0 + wm * TM + i * 32 + sr, col = ncol0 + sc;
-        const u32x4 v = *(const u32x4*)(st + sr * STAGE_BF16 + sc * 2);
-        if (row < a.M && col < a.N) *(u32x4*)((bf16_t*)a.out + (size_t)row * a.ldo + col) = v;
+      for (int half = 0; half < 2; ++half) {
+        if ((lrow >> 4) == half) {
+#pragma unroll
+          for (int j = 0; j < FN; ++j)
+#pragma unroll
+            for (int jj = 0; jj < 4; ++jj)
+              *(u32x2*)(st + (lrow & 15) * D_STAGING_ROW + (j * 32 + jj * 8 + lk * 4) * 2) = pk[j][jj];
+        }
+        __builtin_amdgcn_wave_barrier();
+#pragma unroll
+        for (int p = 0; p < 2; ++p) {  // 8 lanes per row (8 bf16 each), 8 rows per pass
+          const int sr = p * 8 + (lane >> 3), sc = (lane & 7) * 8;
+          const int row = row0 + i * 32 + half * 16 + sr, col = ncol0 + sc;
+          const u32x4 t = *(const u32x4*)(st + sr * D_STAGING_ROW + sc * 2);
+          if (row < a.M && col < a.N) *(u32x4*)((bf16_t*)a.out + (size_t)row * a.ldo + col) = t;
+        }
+        __builtin_amdgcn_wave_barrier();
       }
-      __builtin_amdgcn_wave_barrier();
     }
   }
+}
+
+template <int EPI>
+__global__ __launch_bounds__(512) void gemm_bf16_dma_kernel(const GemmArgs a, int tiles_m, int tiles_n, int n_bands,
+                                                            int n_groups) {
+  constexpr int FM = 4, FN = 2, TM = 128, TN = 64;
+  extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+  unsigned char* staging = smem + D_ST * D_STAGE_BYTES;
+
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int wm = wave >> 2, wn = wave & 3;
+  const int lrow = lane & 31, lk = lane >> 5;
+
+  // ---- tile list of this workgroup: groups xcd, xcd + 8, ...; inside a group the unit's slot picks the tile
+  const int xcd = blockIdx.x & 7, slot = blockIdx.x >> 3;  // slot in [0, 32)
+  const int sm = slot / D_GROUP_N, sn = slot % D_GROUP_N;
+  auto tile_of = [&](int g, int& tm, int& tn) {  // false when the slot has no tile in group g
+    const int mblk = g / n_bands, band = g - mblk * n_bands;
+    tm = mblk * D_GROUP_M + sm;
+    tn = band * D_GROUP_N + sn;
+    return tm < tiles_m && tn < tiles_n;
+  };
+  auto next_group = [&](int g) {  // first group >= g (stride 8) in which this slot has a tile, or n_groups
+    int tm, tn;
+    while (g < n_groups && !tile_of(g, tm, tn)) g += 8;
+    return g < n_groups ? g : n_groups;
+  };
+
+  // ---- loader addressing: one instruction fills 16 tile rows (lane -> row lane/4, LDS chunk lane%4);
+  //      wave w moves rows [32w, 32w + 32) of both operand tiles.  Addresses are a wave-uniform
+  //      64-bit base (scalar registers) plus a per-lane 32-bit byte offset that never changes.
+  const int ld_row = wave * 32 + (lane >> 2);
+  const int ld_chunk = (lane & 3) ^ ((lane >> 4) & 3);  // logical chunk that lands in LDS chunk lane%4
+  const uint32_t offA = (uint32_t)(ld_row * a.lda + ld_chunk * 8) * 2u;
+  const uint32_t offW = (uint32_t)(ld_row * a.ldw + ld_chunk * 8) * 2u;
+  const size_t a_step = (size_t)32 * a.lda, w_step = (size_t)32 * a.ldw;  // bytes per 16 rows
+  const unsigned char *baseA = nullptr, *baseW = nullptr;  // load cursor: uniform tile bases at k = 0
+  int g_l = next_group(xcd), kt_l = 0;
+  auto set_load_tile = [&]() {
+    int tm, tn;
+    if (g_l < n_groups && tile_of(g_l, tm, tn)) {
+      baseA = (const unsigned char*)a.A + (size_t)tm * D_BM * a.lda * 2;
+      baseW = (const unsigned char*)a.W + (size_t)tn * D_BN * a.ldw * 2;
+    }
+  };
+  set_load_tile();
+  // one direct-to-LDS instruction of ring slot `st` at the load cursor: i in [0,2) -> A rows, [2,4) -> W rows
+  auto issue_load = [&](int st, int i) {
+    unsigned char* base = smem + st * D_STAGE_BYTES;
+    if (i < 2)
+      __builtin_amdgcn_global_load_lds((gptr_t)(baseA + i * a_step + kt_l * (D_BK * 2) + offA),
+                                       (lptr_t)(base + (wave * 32 + i * 16) * 64), 16, 0, 0);
+    else
+      __builtin_amdgcn_global_load_lds((gptr_t)(baseW + (i - 2) * w_step + kt_l * (D_BK * 2) + offW),
+                                       (lptr_t)(base + D_BM * 64 + (wave * 32 + (i - 2) * 16) * 64), 16, 0, 0);
+  };
+  const int KT = a.K / D_BK;
+  auto advance_load_cursor = [&]() {
+    if (++kt_l == KT) {
+      kt_l = 0;
+      g_l = next_group(g_l + 8);
+      set_load_tile();
+    }
+  };
+
+  // ---- fragment addressing: row*64 + ((2ks + lk) ^ ((row >> 2) & 3)) * 16, row = 32-aligned base + lrow
+  const int sw = (lrow >> 2) & 3;
+  const uint32_t fa_off0 = (uint32_t)((wm * TM + lrow) * 64 + ((lk ^ sw) << 4));
+  const uint32_t fa_off1 = (uint32_t)((wm * TM + lrow) * 64 + (((2 + lk) ^ sw) << 4));
+  const uint32_t fb_off0 = (uint32_t)(D_BM * 64 + (wn * TN + lrow) * 64 + ((lk ^ sw) << 4));
+  const uint32_t fb_off1 = (uint32_t)(D_BM * 64 + (wn * TN + lrow) * 64 + (((2 + lk) ^ sw) << 4));
+
+  f32x16 acc[FM][FN];
+
+  // One k-step on ring slot st_c; with LOAD the four loads at the load cursor go to ring slot st_l.
+  auto k_step = [&](int st_c, int st_l, auto load_tag) {
+    constexpr bool LOAD = decltype(load_tag)::value;
+    const unsigned char* base = smem + st_c * D_STAGE_BYTES;
+    bf16x8 fa[FM], fb0[FN], fb1[FN];
+    auto rd_a = [&](int ks, int i) { return *(const bf16x8*)(base + (ks ? fa_off1 : fa_off0) + i * 32 * 64); };
+    auto rd_b = [&](int ks, int j) { return *(const bf16x8*)(base + (ks ? fb_off1 : fb_off0) + j * 32 * 64); };
+    auto mm = [&](int i, const bf16x8& x, const bf16x8 (&w)[FN]) {
+#pragma unroll
+      for (int j = 0; j < FN; ++j) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(w[j], x, acc[i][j], 0, 0, 0);
+    };
+    // sched_barrier(0) fences keep each group's instructions together in this order; an A fragment
+    // register is refilled with the second half-step's data as soon as its MFMAs are issued
+    fb0[0] = rd_b(0, 0); fb0[1] = rd_b(0, 1);
+#pragma unroll
+    for (int i = 0; i < FM; ++i) fa[i] = rd_a(0, i);
+    __builtin_amdgcn_sched_barrier(0);
+    mm(0, fa[0], fb0); fb1[0] = rd_b(1, 0); fb1[1] = rd_b(1, 1);
+    if (LOAD) issue_load(st_l, 0);
+    __builtin_amdgcn_sched_barrier(0);
+    mm(1, fa[1], fb0); fa[0] = rd_a(1, 0);
+    __builtin_amdgcn_sched_barrier(0);
+    mm(2, fa[2], fb0); fa[1] = rd_a(1, 1);
+    if (LOAD) issue_load(st_l, 1);
+    __builtin_amdgcn_sched_barrier(0);
+    mm(3, fa[3], fb0); fa[2] = rd_a(1, 2);
+    __builtin_amdgcn_sched_barrier(0);
+    mm(0, fa[0], fb1); fa[3] = rd_a(1, 3);
+    if (LOAD) issue_load(st_l, 2);
+    __builtin_amdgcn_sched_barrier(0);
+    mm(1, fa[1], fb1);
+    __builtin_amdgcn_sched_barrier(0);
+    mm(2, fa[2], fb1);
+    if (LOAD) issue_load(st_l, 3);
+    __builtin_amdgcn_sched_barrier(0);
+    mm(3, fa[3], fb1);
+    __builtin_amdgcn_sched_barrier(0);
+  };
+
+  // ---- how many k-stages this workgroup will load in total
+  int n_my_tiles = 0;
+  for (int g = next_group(xcd); g < n_groups; g = next_group(g + 8)) ++n_my_tiles;
+  const int total_stages = n_my_tiles * KT;
+  int issued = 0, consumed = 0;  // k-stages issued to the ring / multiplied so far
+  int st_c = 0, st_l = 0;
+
+  auto wait_for_stage = [&](bool drain) {
+    // The stage multiplied next must have landed; younger stages (issued - consumed - 1 of them)
+    // may still be in flight.  `drain` also retires the previous epilogue's stores, which share
+    // the counter with the loads.
+    const int young = issued - consumed - 1;
+    if (drain || young <= 0) __builtin_amdgcn_s_waitcnt(0x0F70);              // vmcnt(0)
+    else if (young == 1) __builtin_amdgcn_s_waitcnt(0x0F70 | D_LOADS);        // vmcnt(4)
+    else __builtin_amdgcn_s_waitcnt(0x0F70 | (2 * D_LOADS));                  // vmcnt(8)
+    __builtin_amdgcn_s_barrier();  // everyone's loads of this stage are visible; everyone left the previous step
+  };
+
+  // ---- prologue: fill three ring slots
+  for (int i = 0; i < D_ST - 1 && issued < total_stages; ++i) {
+#pragma unroll
+    for (int j = 0; j < D_LOADS; ++j) issue_load(st_l, j);
+    advance_load_cursor();
+    st_l = (st_l + 1) & (D_ST - 1);
+    ++issued;
+  }
+
+  for (int g_c = next_group(xcd); g_c < n_groups; g_c = next_group(g_c + 8)) {
+#pragma unroll
+    for (int i = 0; i < FM; ++i)
+#pragma unroll
+      for (int j = 0; j < FN; ++j)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
+    // steps that still have a stage to prefetch, then (only at the very end of the list) steps that do not
+    const int n_ld = min(KT, total_stages - issued);
+    for (int kt = 0; kt < n_ld; ++kt) {
+      wait_for_stage(kt == 0);
+      k_step(st_c, st_l, std::true_type{});
+      advance_load_cursor();
+      st_l = (st_l + 1) & (D_ST - 1);
+      st_c = (st_c + 1) & (D_ST - 1);
+      ++issued;
+      ++consumed;
+    }
+    for (int kt = n_ld; kt < KT; ++kt) {
+      wait_for_stage(kt == 0);
+      k_step(st_c, st_l, std::false_type{});
+      st_c = (st_c + 1) & (D_ST - 1);
+      ++consumed;
+    }
+    int tm, tn;
+    tile_of(g_c, tm, tn);
+    asm volatile("" ::: "memory");  // keep the epilogue's loads (bias, residual) below the k-loop
+    wave_epilogue_p<EPI>(a, acc, staging + wave * 16 * D_STAGING_ROW, tm * D_BM + wm * TM, tn * D_BN + wn * TN, lane);
+  }
+}
+
+hipError_t launch_dma(const GemmArgs& a, hipStream_t s) {
+  const int tiles_m = (a.M + D_BM - 1) / D_BM, tiles_n = (a.N + D_BN - 1) / D_BN;
+  const int n_bands = (tiles_n + D_GROUP_N - 1) / D_GROUP_N;
+  const int m_blocks = (tiles_m + D_GROUP_M - 1) / D_GROUP_M;
+  const int n_groups = m_blocks * n_bands;
+  static int n_cu = 0;
+  if (n_cu == 0) {
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return e;
+    e = hipDeviceGetAttribute(&n_cu, hipDeviceAttributeMultiprocessorCount, dev);
+    if (e != hipSuccess) return e;
+  }
+  // one workgroup per compute unit: 8 XCDs x 32 slots (slots beyond the unit count of an XCD stay off)
+  const int grid = 8 * D_GROUP_M * D_GROUP_N;
+  if (n_cu < grid) return hipErrorInvalidValue;
+#define VIT_LAUNCH(EPI)                                                                                              \
+  do {                                                                                                               \
+    auto kfn = gemm_bf16_dma_kernel<EPI>;                                                                            \
+    static bool attr_set = false;                                                                                    \
+    if (!attr_set) {                                                                                                 \
+      hipError_t e = hipFuncSetAttribute((const void*)kfn, hipFuncAttributeMaxDynamicSharedMemorySize, D_LDS_BYTES); \
+      if (e != hipSuccess) return e;                                                                                 \
+      attr_set = true;                                                                                               \
+    }                                                                                                                \
+    hipLaunchKernelGGL(kfn, dim3(grid), dim3(512), D_LDS_BYTES, s, a, tiles_m, tiles_n, n_bands, n_groups);          \
+  } while (0)
+  switch (a.epilogue) {
+    case EPI_BIAS: VIT_LAUNCH(EPI_BIAS); break;
+    case EPI_BIAS_GELU: VIT_LAUNCH(EPI_BIAS_GELU); break;
+    case EPI_BIAS_RESIDUAL: VIT_LAUNCH(EPI_BIAS_RESIDUAL); break;
+    case EPI_PATCH: VIT_LAUNCH(EPI_PATCH); break;
+    default: return hipErrorInvalidValue;
+  }
+#undef VIT_LAUNCH
+  return hipGetLastError();
 }
 
 template <int BM, int BN, int WM, int WN>
@@ -262,7 +619,11 @@ hipError_t launch_gemm_bf16(const GemmArgs& a, hipStream_t s) {
     return hipErrorInvalidValue;
   // Large tiles need enough of them to fill 256 compute units.
   const long big_tiles = (long)((a.M + 255) / 256) * ((a.N + 255) / 256);
+#ifdef VIT_GEMM_NO_DMA
   if (big_tiles >= 512) return launch_cfg<256, 256, 2, 4>(a, s);
+#else
+  if (big_tiles >= 512) return launch_dma(a, s);
+#endif
   return launch_cfg<128, 128, 2, 2>(a, s);
 }
 
