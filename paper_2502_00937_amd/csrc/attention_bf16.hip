@@ -1,6 +1,6 @@
-// Variable-length flash attention on bf16 MFMA.  A work item is a block of query rows of
-// one segment (a tile, or all tiles of an image); keys never come from outside the
-// segment, so no padding or masking crosses images.
+// Variable-length flash attention on bf16 MFMA.  A work item is a block of 128 query rows of
+// one segment (a tile, or all tiles of an image); keys never come from outside the segment, so
+// no padding or masking crosses images.
 //
 // Everything is computed transposed so that a lane owns one query for the whole kernel:
 //   S^T[key, q]  = K[key, :] . Q[q, :]       (A = K tile from LDS, B = Q^T held in registers)
@@ -11,31 +11,46 @@
 // and the P^T operand of the second product is the accumulator of the first, converted in
 // place: registers 8s..8s+7 of an S^T block are exactly the 8 k-values lane group g feeds
 // to k-step s, provided V^T is read in the same key order (keys 16s + 8jj + 4g + i).
+//
+// The softmax arithmetic (exp2, max, sum, convert: plain VALU work) costs more cycles than the
+// two products, so the kernel is shaped around it: a wave owns 64 queries (two 32-query blocks)
+// so every K and V^T fragment read from LDS feeds two MFMAs; the logit scale is folded into the
+// exp2 argument (one fma per element); masking runs only on a segment's last key tile; the
+// output accumulator is rescaled only when some lane's running maximum actually moved; two
+// waves per SIMD (from different workgroups) let one wave's VALU phase overlap the other's MFMAs.
+// K/V tiles of 64 keys are double-buffered in LDS: the next tile's global loads are issued before
+// the current tile is processed and written to the other buffer afterwards (one barrier per tile).
 #include "common.h"
 
 namespace vitenc {
 
 namespace {
 
-constexpr int AQ = 128;   // query rows per workgroup (4 waves x 32)
-constexpr int AKV = 64;   // keys per LDS tile
+constexpr int AQ = 128;  // query rows per workgroup
+constexpr int AKV = 64;  // keys per LDS tile
 
-template <int DHP>
+// QB = 32-query blocks per wave (2 where the registers allow it); the workgroup has 4 / QB waves.
+template <int DHP, int QB>
 struct AttnShape {
-  static constexpr int KS = DHP / 16;               // k-steps of the S^T product
-  static constexpr int DB = (DHP + 31) / 32;        // 32-row blocks of O^T
-  static constexpr int NCH = DHP / 8;               // 16-byte chunks per K/V row
-  static constexpr int K_STRIDE = DHP * 2 + 16;     // bytes per K row in LDS (padding kills bank conflicts)
-  static constexpr int VT_STRIDE = AKV * 2 + 8;     // bytes per V^T row in LDS
+  static constexpr int ANT = 64 * (4 / QB);      // threads per workgroup
+  static constexpr int KS = DHP / 16;            // k-steps of the S^T product
+  static constexpr int DB = (DHP + 31) / 32;     // 32-row blocks of O^T
+  static constexpr int NCH = DHP / 8;            // 16-byte chunks per K/V row
+  static constexpr int K_STRIDE = DHP * 2 + 16;  // bytes per K row in LDS (padding kills bank conflicts)
+  static constexpr int VT_STRIDE = AKV * 2 + 8;  // bytes per V^T row in LDS
   static constexpr int K_BYTES = AKV * K_STRIDE;
   static constexpr int VT_BYTES = DB * 32 * VT_STRIDE;
+  static constexpr int STAGE = K_BYTES + VT_BYTES;
+  static constexpr int K_ITEMS = AKV * NCH;        // 16-byte chunks of the K tile
+  static constexpr int V_ITEMS = (AKV / 2) * NCH;  // (key pair, chunk) items of the V tile
+  static constexpr int K_PER = (K_ITEMS + ANT - 1) / ANT, V_PER = (V_ITEMS + ANT - 1) / ANT;
 };
 
-template <int DHP>
-__global__ __launch_bounds__(256) void attention_bf16_kernel(const AttnArgs a, float scale_log2) {
-  using Sh = AttnShape<DHP>;
-  __shared__ __attribute__((aligned(16))) unsigned char sK[Sh::K_BYTES];
-  __shared__ __attribute__((aligned(16))) unsigned char sVt[Sh::VT_BYTES];
+template <int DHP, int QB>
+__global__ __launch_bounds__(64 * (4 / QB), 2) void attention_bf16_kernel(const AttnArgs a, float scale_log2) {
+  using Sh = AttnShape<DHP, QB>;
+  constexpr int ANT = Sh::ANT;
+  extern __shared__ __attribute__((aligned(16))) unsigned char lds[];  // 2 stages of (K tile, V^T tile)
 
   const AttnWork w = a.work[blockIdx.x];
   const int head = blockIdx.y;
@@ -44,43 +59,46 @@ __global__ __launch_bounds__(256) void attention_bf16_kernel(const AttnArgs a, f
   const bf16_t* base = (const bf16_t*)a.qkv;
   const int qoff = head * DHP, koff = (a.heads + head) * DHP, voff = (2 * a.heads + head) * DHP;
   const int seg_end = w.seg_start + w.seg_len;
-  const int qrow = w.q0 + wave * 32 + lq;
-  const int qload = min(qrow, seg_end - 1);  // rows past the segment end compute on a copy of its last row
 
-  // Q^T fragments: lane holds d = 16*ks + 8*g .. +8 of its query row.
-  bf16x8 qf[Sh::KS];
+  // Q^T fragments of the wave's two query blocks: lane holds d = 16*ks + 8*g .. +8 of its query row;
+  // rows past the segment end compute on a copy of its last row and are never stored.
+  bf16x8 qf[QB][Sh::KS];
 #pragma unroll
-  for (int ks = 0; ks < Sh::KS; ++ks)
-    qf[ks] = *(const bf16x8*)(base + (size_t)qload * a.ld_qkv + qoff + ks * 16 + g * 8);
+  for (int qb = 0; qb < QB; ++qb) {
+    const int qload = min(w.q0 + (wave * QB + qb) * 32 + lq, seg_end - 1);
+#pragma unroll
+    for (int ks = 0; ks < Sh::KS; ++ks)
+      qf[qb][ks] = *(const bf16x8*)(base + (size_t)qload * a.ld_qkv + qoff + ks * 16 + g * 8);
+  }
 
-  f32x16 o[Sh::DB];
+  f32x16 o[QB][Sh::DB];
 #pragma unroll
-  for (int b = 0; b < Sh::DB; ++b)
+  for (int qb = 0; qb < QB; ++qb)
 #pragma unroll
-    for (int v = 0; v < 16; ++v) o[b][v] = 0.f;
-  float m = -INFINITY, l = 0.f;
+    for (int b = 0; b < Sh::DB; ++b)
+#pragma unroll
+      for (int v = 0; v < 16; ++v) o[qb][b][v] = 0.f;
+  float m[QB], l[QB];  // running max (in log2 units) and sum per query
+#pragma unroll
+  for (int qb = 0; qb < QB; ++qb) { m[qb] = -INFINITY; l[qb] = 0.f; }
 
-  constexpr int K_ITEMS = AKV * Sh::NCH;          // 16-byte chunks of the K tile
-  constexpr int V_ITEMS = (AKV / 2) * Sh::NCH;    // (key pair, chunk) items of the V tile
-  constexpr int K_PER = (K_ITEMS + 255) / 256, V_PER = (V_ITEMS + 255) / 256;
-
-  for (int k0 = 0; k0 < w.seg_len; k0 += AKV) {
-    // ---- global -> registers (rows past the segment end are clamped to its last row; their
-    //      logits are masked below, the clamped values only need to be finite)
-    u32x4 rk[K_PER], rv0[V_PER], rv1[V_PER];
+  u32x4 rk[Sh::K_PER], rv0[Sh::V_PER], rv1[Sh::V_PER];
+  // global -> registers; rows past the segment end are clamped to its last row (their logits are
+  // masked, the clamped values only need to be finite)
+  auto load_tile = [&](int k0) {
 #pragma unroll
-    for (int i = 0; i < K_PER; ++i) {
-      const int it = tid + i * 256;
-      if (it < K_ITEMS) {
+    for (int i = 0; i < Sh::K_PER; ++i) {
+      const int it = tid + i * ANT;
+      if (Sh::K_ITEMS % ANT == 0 || it < Sh::K_ITEMS) {
         const int key = it / Sh::NCH, ch = it - key * Sh::NCH;
         const int row = min(w.seg_start + k0 + key, seg_end - 1);
         rk[i] = *(const u32x4*)(base + (size_t)row * a.ld_qkv + koff + ch * 8);
       }
     }
 #pragma unroll
-    for (int i = 0; i < V_PER; ++i) {
-      const int it = tid + i * 256;
-      if (it < V_ITEMS) {
+    for (int i = 0; i < Sh::V_PER; ++i) {
+      const int it = tid + i * ANT;
+      if (Sh::V_ITEMS % ANT == 0 || it < Sh::V_ITEMS) {
         const int ch = it >> 5, kp = it & 31;
         const int r0 = min(w.seg_start + k0 + 2 * kp, seg_end - 1);
         const int r1 = min(w.seg_start + k0 + 2 * kp + 1, seg_end - 1);
@@ -88,110 +106,147 @@ __global__ __launch_bounds__(256) void attention_bf16_kernel(const AttnArgs a, f
         rv1[i] = *(const u32x4*)(base + (size_t)r1 * a.ld_qkv + voff + ch * 8);
       }
     }
-    __syncthreads();  // everyone finished reading the previous tile
+  };
+  // registers -> LDS; V is transposed on the way in: V^T[d][2kp], V^T[d][2kp+1] packed into one word
+  auto store_tile = [&](unsigned char* sK, unsigned char* sVt) {
 #pragma unroll
-    for (int i = 0; i < K_PER; ++i) {
-      const int it = tid + i * 256;
-      if (it < K_ITEMS) {
+    for (int i = 0; i < Sh::K_PER; ++i) {
+      const int it = tid + i * ANT;
+      if (Sh::K_ITEMS % ANT == 0 || it < Sh::K_ITEMS) {
         const int key = it / Sh::NCH, ch = it - key * Sh::NCH;
         *(u32x4*)(sK + key * Sh::K_STRIDE + ch * 16) = rk[i];
       }
     }
 #pragma unroll
-    for (int i = 0; i < V_PER; ++i) {
-      const int it = tid + i * 256;
-      if (it < V_ITEMS) {
+    for (int i = 0; i < Sh::V_PER; ++i) {
+      const int it = tid + i * ANT;
+      if (Sh::V_ITEMS % ANT == 0 || it < Sh::V_ITEMS) {
         const int ch = it >> 5, kp = it & 31;
-        // transpose on the way in: V^T[d][2kp], V^T[d][2kp+1] packed into one 32-bit word
 #pragma unroll
         for (int e = 0; e < 4; ++e) {
           const uint32_t x0 = rv0[i][e], x1 = rv1[i][e];
-          const uint32_t lo = (x0 & 0xFFFFu) | (x1 << 16);
-          const uint32_t hi = (x0 >> 16) | (x1 & 0xFFFF0000u);
-          *(uint32_t*)(sVt + (ch * 8 + 2 * e) * Sh::VT_STRIDE + kp * 4) = lo;
-          *(uint32_t*)(sVt + (ch * 8 + 2 * e + 1) * Sh::VT_STRIDE + kp * 4) = hi;
+          *(uint32_t*)(sVt + (ch * 8 + 2 * e) * Sh::VT_STRIDE + kp * 4) = (x0 & 0xFFFFu) | (x1 << 16);
+          *(uint32_t*)(sVt + (ch * 8 + 2 * e + 1) * Sh::VT_STRIDE + kp * 4) = (x0 >> 16) | (x1 & 0xFFFF0000u);
         }
       }
     }
-    __syncthreads();
+  };
 
-    // ---- S^T = K . Q^T for the two 32-key blocks of the tile
-    f32x16 st[2];
+  const int n_tiles = (w.seg_len + AKV - 1) / AKV;
+  load_tile(0);
+  store_tile(lds, lds + Sh::K_BYTES);
+  __syncthreads();
+
+  for (int t = 0; t < n_tiles; ++t) {
+    const unsigned char* sK = lds + (t & 1) * Sh::STAGE;
+    const unsigned char* sVt = sK + Sh::K_BYTES;
+    if (t + 1 < n_tiles) load_tile((t + 1) * AKV);
+
+    const int remaining = w.seg_len - t * AKV;  // valid keys in this tile (may exceed AKV)
+    // the tile is processed in two 32-key halves to keep S^T and P^T small in registers
 #pragma unroll
     for (int kb = 0; kb < 2; ++kb) {
+      // ---- S^T = K . Q^T: each K fragment feeds all query blocks of the wave
+      f32x16 st[QB];
 #pragma unroll
-      for (int v = 0; v < 16; ++v) st[kb][v] = 0.f;
+      for (int qb = 0; qb < QB; ++qb)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) st[qb][v] = 0.f;
 #pragma unroll
       for (int ks = 0; ks < Sh::KS; ++ks) {
         const bf16x8 kf = *(const bf16x8*)(sK + (kb * 32 + lq) * Sh::K_STRIDE + (ks * 2 + g) * 16);
-        st[kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[ks], st[kb], 0, 0, 0);
+#pragma unroll
+        for (int qb = 0; qb < QB; ++qb)
+          st[qb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[qb][ks], st[qb], 0, 0, 0);
       }
-    }
-    // ---- scale, mask keys past the segment end, running max
-    const int remaining = w.seg_len - k0;  // valid keys in this tile (may exceed AKV)
-    float mx = -INFINITY;
+      // ---- mask keys past the segment end (only a segment's last tile has any)
+      if (remaining < AKV) {
 #pragma unroll
-    for (int kb = 0; kb < 2; ++kb)
+        for (int qb = 0; qb < QB; ++qb)
 #pragma unroll
-      for (int v = 0; v < 16; ++v) {
-        const int key = kb * 32 + 8 * (v >> 2) + 4 * g + (v & 3);
-        float s = st[kb][v] * scale_log2;
-        s = key < remaining ? s : -INFINITY;
-        st[kb][v] = s;
-        mx = fmaxf(mx, s);
+          for (int v = 0; v < 16; ++v) {
+            const int key = kb * 32 + 8 * (v >> 2) + 4 * g + (v & 3);
+            if (key >= remaining) st[qb][v] = -INFINITY;
+          }
       }
-    mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
-    const float m_new = fmaxf(m, mx);
-    const float corr = __builtin_amdgcn_exp2f(m - m_new);
-    m = m_new;
-    float psum = 0.f;
-    bf16x8 pf[2][2];
+      // ---- online softmax per query block; P^T replaces S^T as bf16 fragments
+      bf16x8 pf[QB][2];
 #pragma unroll
-    for (int kb = 0; kb < 2; ++kb)
+      for (int qb = 0; qb < QB; ++qb) {
+        float mx = st[qb][0];
 #pragma unroll
-      for (int s2 = 0; s2 < 2; ++s2)
+        for (int v = 1; v < 16; ++v) mx = fmaxf(mx, st[qb][v]);
+        mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
+        const float m_new = fmaxf(m[qb], mx * scale_log2);
+        // rescale the output accumulator only if some query's maximum moved
+        if (__builtin_amdgcn_ballot_w64(m_new != m[qb]) != 0) {
+          const float corr = __builtin_amdgcn_exp2f(m[qb] - m_new);
+          l[qb] *= corr;
 #pragma unroll
-        for (int e = 0; e < 8; ++e) {
-          const float p = __builtin_amdgcn_exp2f(st[kb][s2 * 8 + e] - m_new);
-          psum += p;
-          pf[kb][s2][e] = (__bf16)p;
+          for (int b = 0; b < Sh::DB; ++b)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) o[qb][b][v] *= corr;
+          m[qb] = m_new;
         }
-    l = l * corr + psum;
+        const float neg_m = -m[qb];
+        float psum = 0.f;
 #pragma unroll
-    for (int b = 0; b < Sh::DB; ++b)
+        for (int s2 = 0; s2 < 2; ++s2) {
+          float p[8];
 #pragma unroll
-      for (int v = 0; v < 16; ++v) o[b][v] *= corr;
-    // ---- O^T += V^T . P^T
+          for (int e = 0; e < 8; ++e) {
+            p[e] = __builtin_amdgcn_exp2f(fmaf(st[qb][s2 * 8 + e], scale_log2, neg_m));
+            psum += p[e];
+          }
+          const u32x4 pk = {pack_bf16x2(p[0], p[1]), pack_bf16x2(p[2], p[3]), pack_bf16x2(p[4], p[5]),
+                            pack_bf16x2(p[6], p[7])};
+          pf[qb][s2] = __builtin_bit_cast(bf16x8, pk);
+        }
+        l[qb] += psum;
+      }
+      // ---- O^T += V^T . P^T: each V^T fragment feeds all query blocks of the wave
 #pragma unroll
-    for (int b = 0; b < Sh::DB; ++b)
-#pragma unroll
-      for (int kb = 0; kb < 2; ++kb)
+      for (int b = 0; b < Sh::DB; ++b)
 #pragma unroll
         for (int s2 = 0; s2 < 2; ++s2) {
           const unsigned char* p = sVt + (b * 32 + lq) * Sh::VT_STRIDE + (kb * 32 + s2 * 16 + 4 * g) * 2;
           const u32x2 lo = *(const u32x2*)p, hi = *(const u32x2*)(p + 16);
           const u32x4 packed = {lo[0], lo[1], hi[0], hi[1]};
-          o[b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, packed), pf[kb][s2], o[b], 0, 0, 0);
+          const bf16x8 vf = __builtin_bit_cast(bf16x8, packed);
+#pragma unroll
+          for (int qb = 0; qb < QB; ++qb)
+            o[qb][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, pf[qb][s2], o[qb][b], 0, 0, 0);
         }
+    }
+
+    if (t + 1 < n_tiles) {
+      unsigned char* nK = lds + ((t + 1) & 1) * Sh::STAGE;
+      store_tile(nK, nK + Sh::K_BYTES);
+    }
+    __syncthreads();
   }
 
-  // ---- normalise and store: lane owns query qrow; registers 4j..4j+3 of block b are
+  // ---- normalise and store: lane owns a query; registers 4j..4j+3 of block b are
   //      d = 32b + 8j + 4g .. +3, four consecutive columns -> one 8-byte store
-  l += __shfl_xor(l, 32, 64);
-  if (qrow < seg_end) {
-    const float inv = 1.0f / l;
-    bf16_t* orow = (bf16_t*)a.out + (size_t)qrow * a.ld_o + head * DHP;
 #pragma unroll
-    for (int b = 0; b < Sh::DB; ++b)
+  for (int qb = 0; qb < QB; ++qb) {
+    const int qrow = w.q0 + (wave * QB + qb) * 32 + lq;
+    const float lsum = l[qb] + __shfl_xor(l[qb], 32, 64);
+    if (qrow < seg_end) {
+      const float inv = 1.0f / lsum;
+      bf16_t* orow = (bf16_t*)a.out + (size_t)qrow * a.ld_o + head * DHP;
 #pragma unroll
-      for (int j = 0; j < 4; ++j) {
-        const int d = b * 32 + 8 * j + 4 * g;
-        if (d < DHP) {
-          const u32x2 pk = {pack_bf16x2(o[b][4 * j] * inv, o[b][4 * j + 1] * inv),
-                            pack_bf16x2(o[b][4 * j + 2] * inv, o[b][4 * j + 3] * inv)};
-          *(u32x2*)(orow + d) = pk;
+      for (int b = 0; b < Sh::DB; ++b)
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+          const int d = b * 32 + 8 * j + 4 * g;
+          if (d < DHP) {
+            const u32x2 pk = {pack_bf16x2(o[qb][b][4 * j] * inv, o[qb][b][4 * j + 1] * inv),
+                              pack_bf16x2(o[qb][b][4 * j + 2] * inv, o[qb][b][4 * j + 3] * inv)};
+            *(u32x2*)(orow + d) = pk;
+          }
         }
-      }
+    }
   }
 }
 
@@ -203,14 +258,27 @@ hipError_t launch_attention_bf16(const AttnArgs& a, hipStream_t s) {
   if (a.n_work <= 0) return hipSuccess;
   if (a.ld_qkv % 8 != 0 || a.ld_o % 4 != 0) return hipErrorInvalidValue;
   const float scale_log2 = 1.4426950408889634f / sqrtf((float)a.dh);
-  const dim3 grid(a.n_work, a.heads), block(256);
+  const dim3 grid(a.n_work, a.heads);
+#define VIT_ATTN(DHP, QB)                                                                              \
+  do {                                                                                                 \
+    constexpr int smem = 2 * AttnShape<DHP, QB>::STAGE;                                                \
+    auto kfn = attention_bf16_kernel<DHP, QB>;                                                         \
+    static bool attr_set = false; /* the dynamic LDS limit is raised once per kernel */                \
+    if (!attr_set) {                                                                                   \
+      hipError_t e = hipFuncSetAttribute((const void*)kfn, hipFuncAttributeMaxDynamicSharedMemorySize, smem); \
+      if (e != hipSuccess) return e;                                                                   \
+      attr_set = true;                                                                                 \
+    }                                                                                                  \
+    hipLaunchKernelGGL(kfn, grid, dim3(AttnShape<DHP, QB>::ANT), smem, s, a, scale_log2);              \
+  } while (0)
   switch (a.dh_pad) {
-    case 64: hipLaunchKernelGGL(attention_bf16_kernel<64>, grid, block, 0, s, a, scale_log2); break;
-    case 80: hipLaunchKernelGGL(attention_bf16_kernel<80>, grid, block, 0, s, a, scale_log2); break;
-    case 96: hipLaunchKernelGGL(attention_bf16_kernel<96>, grid, block, 0, s, a, scale_log2); break;
-    case 128: hipLaunchKernelGGL(attention_bf16_kernel<128>, grid, block, 0, s, a, scale_log2); break;
+    case 64: VIT_ATTN(64, 2); break;
+    case 80: VIT_ATTN(80, 1); break;
+    case 96: VIT_ATTN(96, 1); break;
+    case 128: VIT_ATTN(128, 1); break;
     default: return hipErrorInvalidValue;
   }
+#undef VIT_ATTN
   return hipGetLastError();
 }
 
