@@ -264,15 +264,10 @@ typedef __attribute__((address_space(3))) void* lptr_t;
 // Epilogue of one wave of the persistent kernel: same register layout as wave_epilogue, but staged
 // 16 rows at a time through the wave's private 16 x 144-byte LDS rows (`st`).
 template <int EPI>
-__device__ __forceinline__ void wave_epilogue_p(const GemmArgs& a, f32x16 (&acc)[4][2], unsigned char* st, int row0,
-                                                int ncol0, int lane) {
+__device__ __forceinline__ void wave_epilogue_p(const GemmArgs& a, f32x16 (&acc)[4][2], const f32x4 (&bias)[2][4],
+                                                unsigned char* st, int row0, int ncol0, int lane) {
   constexpr int FM = 4, FN = 2;
   const int lrow = lane & 31, lk = lane >> 5;
-  f32x4 bias[FN][4];
-#pragma unroll
-  for (int j = 0; j < FN; ++j)
-#pragma unroll
-    for (int jj = 0; jj < 4; ++jj) bias[j][jj] = *(const f32x4*)(a.bias + ncol0 + j * 32 + jj * 8 + lk * 4);
 
   if constexpr (EPI == EPI_PATCH) {
 #pragma unroll
@@ -297,39 +292,51 @@ __device__ __forceinline__ void wave_epilogue_p(const GemmArgs& a, f32x16 (&acc)
         }
     }
   } else if constexpr (EPI == EPI_BIAS_RESIDUAL) {
-    // pieces of 16 rows x 32 fp32 columns (128 bytes + pad per staged row)
+    // Pieces of 16 rows x 32 fp32 columns (128 bytes + pad per staged row); a piece is read back
+    // as 8 lanes per row, 8 rows per pass.  The residual values of a 32 x 32 unit (2 pieces of
+    // 2 passes) are loaded one unit ahead so their latency hides behind the previous unit.
+    const int sr0 = lane >> 3, sc = (lane & 7) * 4;
+    auto x_ptr = [&](int i, int j, int half, int p) {
+      return a.resid + (size_t)(row0 + i * 32 + half * 16 + p * 8 + sr0) * a.ldo + ncol0 + j * 32 + sc;
+    };
+    auto x_ok = [&](int i, int j, int half, int p) {
+      return row0 + i * 32 + half * 16 + p * 8 + sr0 < a.M && ncol0 + j * 32 + sc < a.N;
+    };
+    f32x4 xin[2][2][2];  // [buffer][half][pass] of one (row block, column block) unit
+    auto load_unit = [&](int u, int buf) {  // unit u = i * FN + j
+      const int i = u / FN, j = u % FN;
 #pragma unroll
-    for (int i = 0; i < FM; ++i)
+      for (int half = 0; half < 2; ++half)
 #pragma unroll
-      for (int j = 0; j < FN; ++j) {
-        f32x4 v[4];
+        for (int p = 0; p < 2; ++p)
+          xin[buf][half][p] = x_ok(i, j, half, p) ? *(const f32x4*)x_ptr(i, j, half, p) : f32x4{0.f, 0.f, 0.f, 0.f};
+    };
+    load_unit(0, 0);
 #pragma unroll
-        for (int jj = 0; jj < 4; ++jj)
+    for (int u = 0; u < FM * FN; ++u) {
+      const int i = u / FN, j = u % FN;
+      if (u + 1 < FM * FN) load_unit(u + 1, (u + 1) & 1);
+      f32x4 v[4];
 #pragma unroll
-          for (int e = 0; e < 4; ++e) v[jj][e] = acc[i][j][jj * 4 + e] + bias[j][jj][e];
+      for (int jj = 0; jj < 4; ++jj)
 #pragma unroll
-        for (int half = 0; half < 2; ++half) {
-          if ((lrow >> 4) == half) {
+        for (int e = 0; e < 4; ++e) v[jj][e] = acc[i][j][jj * 4 + e] + bias[j][jj][e];
 #pragma unroll
-            for (int jj = 0; jj < 4; ++jj)
-              *(f32x4*)(st + (lrow & 15) * D_STAGING_ROW + (jj * 8 + lk * 4) * 4) = v[jj];
-          }
-          __builtin_amdgcn_wave_barrier();
+      for (int half = 0; half < 2; ++half) {
+        if ((lrow >> 4) == half) {
 #pragma unroll
-          for (int p = 0; p < 2; ++p) {  // 8 lanes per row (16 bytes each), 8 rows per pass
-            const int sr = p * 8 + (lane >> 3), sc = (lane & 7) * 4;
-            const int row = row0 + i * 32 + half * 16 + sr, col = ncol0 + j * 32 + sc;
-            const f32x4 t = *(const f32x4*)(st + sr * D_STAGING_ROW + sc * 4);
-            if (row < a.M && col < a.N) {
-              float* xp = a.resid + (size_t)row * a.ldo + col;
-              f32x4 x = *(const f32x4*)xp;
-              x += t;
-              *(f32x4*)xp = x;
-            }
-          }
-          __builtin_amdgcn_wave_barrier();
+          for (int jj = 0; jj < 4; ++jj)
+            *(f32x4*)(st + (lrow & 15) * D_STAGING_ROW + (jj * 8 + lk * 4) * 4) = v[jj];
         }
+        __builtin_amdgcn_wave_barrier();
+#pragma unroll
+        for (int p = 0; p < 2; ++p) {
+          const f32x4 t = *(const f32x4*)(st + (p * 8 + sr0) * D_STAGING_ROW + sc * 4);
+          if (x_ok(i, j, half, p)) *(f32x4*)x_ptr(i, j, half, p) = xin[u & 1][half][p] + t;
+        }
+        __builtin_amdgcn_wave_barrier();
       }
+    }
   } else {  // EPI_BIAS, EPI_BIAS_GELU: bf16 output, pieces of 16 rows x 64 columns (128 bytes + pad)
 #pragma unroll
     for (int i = 0; i < FM; ++i) {
@@ -487,14 +494,18 @@ __global__ __launch_bounds__(512) void gemm_bf16_dma_kernel(const GemmArgs a, in
   int issued = 0, consumed = 0;  // k-stages issued to the ring / multiplied so far
   int st_c = 0, st_l = 0;
 
-  auto wait_for_stage = [&](bool drain) {
-    // The stage multiplied next must have landed; younger stages (issued - consumed - 1 of them)
-    // may still be in flight.  `drain` also retires the previous epilogue's stores, which share
-    // the counter with the loads.
-    const int young = issued - consumed - 1;
-    if (drain || young <= 0) __builtin_amdgcn_s_waitcnt(0x0F70);              // vmcnt(0)
-    else if (young == 1) __builtin_amdgcn_s_waitcnt(0x0F70 | D_LOADS);        // vmcnt(4)
-    else __builtin_amdgcn_s_waitcnt(0x0F70 | (2 * D_LOADS));                  // vmcnt(8)
+  int landed = 0;  // stages [0, landed) are known to have landed (the ring was drained after they were issued)
+  auto wait_for_stage = [&]() {
+    // The stage multiplied next must have landed; the `young` stages issued after it may be in
+    // flight.  The vector-memory counter also counts the epilogue's stores, whose completion order
+    // relative to loads is not relied on: "at most young*4 operations outstanding" bounds the
+    // outstanding loads from above, and loads complete in issue order.
+    if (consumed >= landed) {
+      const int young = issued - consumed - 1;
+      if (young <= 0) __builtin_amdgcn_s_waitcnt(0x0F70);                       // vmcnt(0)
+      else if (young == 1) __builtin_amdgcn_s_waitcnt(0x0F70 | D_LOADS);        // vmcnt(4)
+      else __builtin_amdgcn_s_waitcnt(0x0F70 | (2 * D_LOADS));                  // vmcnt(8)
+    }
     __builtin_amdgcn_s_barrier();  // everyone's loads of this stage are visible; everyone left the previous step
   };
 
@@ -514,10 +525,13 @@ __global__ __launch_bounds__(512) void gemm_bf16_dma_kernel(const GemmArgs a, in
       for (int j = 0; j < FN; ++j)
 #pragma unroll
         for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
+    int tm, tn;
+    tile_of(g_c, tm, tn);
+    const int row0 = tm * D_BM + wm * TM, ncol0 = tn * D_BN + wn * TN;
     // steps that still have a stage to prefetch, then (only at the very end of the list) steps that do not
     const int n_ld = min(KT, total_stages - issued);
     for (int kt = 0; kt < n_ld; ++kt) {
-      wait_for_stage(kt == 0);
+      wait_for_stage();
       k_step(st_c, st_l, std::true_type{});
       advance_load_cursor();
       st_l = (st_l + 1) & (D_ST - 1);
@@ -526,15 +540,23 @@ __global__ __launch_bounds__(512) void gemm_bf16_dma_kernel(const GemmArgs a, in
       ++consumed;
     }
     for (int kt = n_ld; kt < KT; ++kt) {
-      wait_for_stage(kt == 0);
+      wait_for_stage();
       k_step(st_c, st_l, std::false_type{});
       st_c = (st_c + 1) & (D_ST - 1);
       ++consumed;
     }
-    int tm, tn;
-    tile_of(g_c, tm, tn);
-    asm volatile("" ::: "memory");  // keep the epilogue's loads (bias, residual) below the k-loop
-    wave_epilogue_p<EPI>(a, acc, staging + wave * 16 * D_STAGING_ROW, tm * D_BM + wm * TM, tn * D_BN + wn * TN, lane);
+    asm volatile("" ::: "memory");  // keep the epilogue's loads below the k-loop
+    // The epilogue's first loads (bias, residual rows) queue behind the operand ring, so waiting for
+    // them drains the ring: every stage issued so far has landed and the next tile's first steps
+    // need no counter wait.  The epilogue's stores are never waited for explicitly.
+    f32x4 bias[FN][4];
+#pragma unroll
+    for (int j = 0; j < FN; ++j)
+#pragma unroll
+      for (int jj = 0; jj < 4; ++jj) bias[j][jj] = *(const f32x4*)(a.bias + ncol0 + j * 32 + jj * 8 + lk * 4);
+    __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0)
+    landed = issued;
+    wave_epilogue_p<EPI>(a, acc, bias, staging + wave * 16 * D_STAGING_ROW, row0, ncol0, lane);
   }
 }
 
