@@ -447,44 +447,17 @@ __global__ __launch_bounds__(512) void gemm_bf16_dma_kernel(const GemmArgs a, in
   const uint32_t fb_off1 = (uint32_t)(D_BM * 64 + (wn * TN + lrow) * 64 + (((2 + lk) ^ sw) << 4));
 
   f32x16 acc[FM][FN];
+  bf16x8 fa0[FM], fb0[FN], fa1[FM], fb1[FN];  // fragments of the two 16-wide halves of a k-step
 
-  // One k-step on ring slot st_c; with LOAD the four loads at the load cursor go to ring slot st_l.
-  auto k_step = [&](int st_c, int st_l, auto load_tag) {
-    constexpr bool LOAD = decltype(load_tag)::value;
-    const unsigned char* base = smem + st_c * D_STAGE_BYTES;
-    bf16x8 fa[FM], fb0[FN], fb1[FN];
-    auto rd_a = [&](int ks, int i) { return *(const bf16x8*)(base + (ks ? fa_off1 : fa_off0) + i * 32 * 64); };
-    auto rd_b = [&](int ks, int j) { return *(const bf16x8*)(base + (ks ? fb_off1 : fb_off0) + j * 32 * 64); };
-    auto mm = [&](int i, const bf16x8& x, const bf16x8 (&w)[FN]) {
+  auto rd_a = [&](int st, int ks, int i) {
+    return *(const bf16x8*)(smem + st * D_STAGE_BYTES + (ks ? fa_off1 : fa_off0) + i * 32 * 64);
+  };
+  auto rd_b = [&](int st, int ks, int j) {
+    return *(const bf16x8*)(smem + st * D_STAGE_BYTES + (ks ? fb_off1 : fb_off0) + j * 32 * 64);
+  };
+  auto mm = [&](int i, const bf16x8& x, const bf16x8 (&w)[FN]) {
 #pragma unroll
-      for (int j = 0; j < FN; ++j) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(w[j], x, acc[i][j], 0, 0, 0);
-    };
-    // sched_barrier(0) fences keep each group's instructions together in this order; an A fragment
-    // register is refilled with the second half-step's data as soon as its MFMAs are issued
-    fb0[0] = rd_b(0, 0); fb0[1] = rd_b(0, 1);
-#pragma unroll
-    for (int i = 0; i < FM; ++i) fa[i] = rd_a(0, i);
-    __builtin_amdgcn_sched_barrier(0);
-    mm(0, fa[0], fb0); fb1[0] = rd_b(1, 0); fb1[1] = rd_b(1, 1);
-    if (LOAD) issue_load(st_l, 0);
-    __builtin_amdgcn_sched_barrier(0);
-    mm(1, fa[1], fb0); fa[0] = rd_a(1, 0);
-    __builtin_amdgcn_sched_barrier(0);
-    mm(2, fa[2], fb0); fa[1] = rd_a(1, 1);
-    if (LOAD) issue_load(st_l, 1);
-    __builtin_amdgcn_sched_barrier(0);
-    mm(3, fa[3], fb0); fa[2] = rd_a(1, 2);
-    __builtin_amdgcn_sched_barrier(0);
-    mm(0, fa[0], fb1); fa[3] = rd_a(1, 3);
-    if (LOAD) issue_load(st_l, 2);
-    __builtin_amdgcn_sched_barrier(0);
-    mm(1, fa[1], fb1);
-    __builtin_amdgcn_sched_barrier(0);
-    mm(2, fa[2], fb1);
-    if (LOAD) issue_load(st_l, 3);
-    __builtin_amdgcn_sched_barrier(0);
-    mm(3, fa[3], fb1);
-    __builtin_amdgcn_sched_barrier(0);
+    for (int j = 0; j < FN; ++j) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(w[j], x, acc[i][j], 0, 0, 0);
   };
 
   // ---- how many k-stages this workgroup will load in total
@@ -492,30 +465,83 @@ __global__ __launch_bounds__(512) void gemm_bf16_dma_kernel(const GemmArgs a, in
   for (int g = next_group(xcd); g < n_groups; g = next_group(g + 8)) ++n_my_tiles;
   const int total_stages = n_my_tiles * KT;
   int issued = 0, consumed = 0;  // k-stages issued to the ring / multiplied so far
-  int st_c = 0, st_l = 0;
-
   int landed = 0;  // stages [0, landed) are known to have landed (the ring was drained after they were issued)
-  auto wait_for_stage = [&]() {
-    // The stage multiplied next must have landed; the `young` stages issued after it may be in
-    // flight.  The vector-memory counter also counts the epilogue's stores, whose completion order
-    // relative to loads is not relied on: "at most young*4 operations outstanding" bounds the
-    // outstanding loads from above, and loads complete in issue order.
-    if (consumed >= landed) {
-      const int young = issued - consumed - 1;
-      if (young <= 0) __builtin_amdgcn_s_waitcnt(0x0F70);                       // vmcnt(0)
-      else if (young == 1) __builtin_amdgcn_s_waitcnt(0x0F70 | D_LOADS);        // vmcnt(4)
-      else __builtin_amdgcn_s_waitcnt(0x0F70 | (2 * D_LOADS));                  // vmcnt(8)
-    }
-    __builtin_amdgcn_s_barrier();  // everyone's loads of this stage are visible; everyone left the previous step
+  int st_c = 0;    // ring slot of the stage being multiplied
+
+  // Wait until stage `s` has landed for this wave (its own loads), then meet the other waves.
+  // Stages issued after `s` may be in flight.  The vector-memory counter also counts the epilogue's
+  // stores; "at most young*4 operations outstanding" bounds the outstanding loads from above and
+  // loads complete in issue order, so the wait is sufficient whatever the stores do.  All LDS
+  // reads of this wave are complete before the barrier (lgkmcnt(0)), so the slot read last may be
+  // overwritten by loads issued after the barrier.
+  auto sync_stage = [&](int s) {
+    const int young = issued - s - 1;
+    if (s < landed || young >= 4) __builtin_amdgcn_s_waitcnt(0xC07F);  // lgkmcnt(0) only
+    else if (young == 3) __builtin_amdgcn_s_waitcnt(0x007C);          // vmcnt(12) lgkmcnt(0)
+    else if (young == 2) __builtin_amdgcn_s_waitcnt(0x0078);          // vmcnt(8)
+    else if (young == 1) __builtin_amdgcn_s_waitcnt(0x0074);          // vmcnt(4)
+    else __builtin_amdgcn_s_waitcnt(0x0070);                          // vmcnt(0)
+    __builtin_amdgcn_s_barrier();
   };
 
-  // ---- prologue: fill three ring slots
-  for (int i = 0; i < D_ST - 1 && issued < total_stages; ++i) {
+  // One k-step, software-pipelined across the step boundary.
+  //   phase A: MFMAs of the first half (fragments already in registers) while the second half's
+  //            fragments are read;
+  //   middle:  the next stage must have landed for every wave (barrier); the barrier wait and the
+  //            LDS latency of the reads that follow hide behind the MFMAs already queued;
+  //   phase B: MFMAs of the second half while the NEXT step's first-half fragments are read and
+  //            the four loads of the stage four steps ahead go into the slot this step just freed.
+  // sched_barrier(0) fences keep each group's instructions together in this order.
+  auto k_step = [&](auto load_tag, auto next_tag) {
+    constexpr bool LOAD = decltype(load_tag)::value, NEXT = decltype(next_tag)::value;
+    const int sn = (st_c + 1) & (D_ST - 1);
+    fb1[0] = rd_b(st_c, 1, 0); fb1[1] = rd_b(st_c, 1, 1);
+    fa1[0] = rd_a(st_c, 1, 0);
+    __builtin_amdgcn_sched_barrier(0);
+    mm(0, fa0[0], fb0); fa1[1] = rd_a(st_c, 1, 1);
+    __builtin_amdgcn_sched_barrier(0);
+    mm(1, fa0[1], fb0); fa1[2] = rd_a(st_c, 1, 2);
+    __builtin_amdgcn_sched_barrier(0);
+    mm(2, fa0[2], fb0); fa1[3] = rd_a(st_c, 1, 3);
+    __builtin_amdgcn_sched_barrier(0);
+    mm(3, fa0[3], fb0);
+    __builtin_amdgcn_sched_barrier(0);
+    if (NEXT) sync_stage(consumed + 1);
+    __builtin_amdgcn_sched_barrier(0);
+    if (NEXT) { fb0[0] = rd_b(sn, 0, 0); fb0[1] = rd_b(sn, 0, 1); fa0[0] = rd_a(sn, 0, 0); }
+    __builtin_amdgcn_sched_barrier(0);
+    mm(0, fa1[0], fb1);
+    if (NEXT) fa0[1] = rd_a(sn, 0, 1);
+    if (LOAD) issue_load(st_c, 0);
+    __builtin_amdgcn_sched_barrier(0);
+    mm(1, fa1[1], fb1);
+    if (NEXT) fa0[2] = rd_a(sn, 0, 2);
+    if (LOAD) issue_load(st_c, 1);
+    __builtin_amdgcn_sched_barrier(0);
+    mm(2, fa1[2], fb1);
+    if (NEXT) fa0[3] = rd_a(sn, 0, 3);
+    if (LOAD) issue_load(st_c, 2);
+    __builtin_amdgcn_sched_barrier(0);
+    mm(3, fa1[3], fb1);
+    if (LOAD) issue_load(st_c, 3);
+    __builtin_amdgcn_sched_barrier(0);
+    if (LOAD) { advance_load_cursor(); ++issued; }
+    ++consumed;
+    st_c = sn;
+  };
+
+  // ---- prologue: fill the ring, wait for the first stage, read its first-half fragments
+  for (int i = 0; i < D_ST && issued < total_stages; ++i) {
 #pragma unroll
-    for (int j = 0; j < D_LOADS; ++j) issue_load(st_l, j);
+    for (int j = 0; j < D_LOADS; ++j) issue_load(i, j);
     advance_load_cursor();
-    st_l = (st_l + 1) & (D_ST - 1);
     ++issued;
+  }
+  if (total_stages > 0) {
+    sync_stage(0);
+    fb0[0] = rd_b(0, 0, 0); fb0[1] = rd_b(0, 0, 1);
+#pragma unroll
+    for (int i = 0; i < FM; ++i) fa0[i] = rd_a(0, 0, i);
   }
 
   for (int g_c = next_group(xcd); g_c < n_groups; g_c = next_group(g_c + 8)) {
@@ -528,27 +554,17 @@ __global__ __launch_bounds__(512) void gemm_bf16_dma_kernel(const GemmArgs a, in
     int tm, tn;
     tile_of(g_c, tm, tn);
     const int row0 = tm * D_BM + wm * TM, ncol0 = tn * D_BN + wn * TN;
-    // steps that still have a stage to prefetch, then (only at the very end of the list) steps that do not
+    // steps that still prefetch a stage; then (only at the end of the list) steps that only read
+    // ahead; then the very last step of the list, which has nothing after it
     const int n_ld = min(KT, total_stages - issued);
-    for (int kt = 0; kt < n_ld; ++kt) {
-      wait_for_stage();
-      k_step(st_c, st_l, std::true_type{});
-      advance_load_cursor();
-      st_l = (st_l + 1) & (D_ST - 1);
-      st_c = (st_c + 1) & (D_ST - 1);
-      ++issued;
-      ++consumed;
-    }
-    for (int kt = n_ld; kt < KT; ++kt) {
-      wait_for_stage();
-      k_step(st_c, st_l, std::false_type{});
-      st_c = (st_c + 1) & (D_ST - 1);
-      ++consumed;
-    }
+    const int n_nx = min(KT, total_stages - 1 - consumed);
+    for (int kt = 0; kt < n_ld; ++kt) k_step(std::true_type{}, std::true_type{});
+    for (int kt = n_ld; kt < n_nx; ++kt) k_step(std::false_type{}, std::true_type{});
+    for (int kt = max(n_ld, n_nx); kt < KT; ++kt) k_step(std::false_type{}, std::false_type{});
     asm volatile("" ::: "memory");  // keep the epilogue's loads below the k-loop
     // The epilogue's first loads (bias, residual rows) queue behind the operand ring, so waiting for
-    // them drains the ring: every stage issued so far has landed and the next tile's first steps
-    // need no counter wait.  The epilogue's stores are never waited for explicitly.
+    // them drains the ring: every stage issued so far has landed and the next steps need no counter
+    // wait for them.  The epilogue's stores are never waited for explicitly.
     f32x4 bias[FN][4];
 #pragma unroll
     for (int j = 0; j < FN; ++j)
