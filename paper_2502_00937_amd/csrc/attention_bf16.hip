@@ -28,6 +28,7 @@ namespace {
 
 constexpr int AQ = 128;  // query rows per workgroup
 constexpr int AKV = 64;  // keys per LDS tile
+constexpr float RESCALE_SLACK = 8.0f;  // log2 units the logits may exceed the reference maximum by
 
 // QB = 32-query blocks per wave (2 where the registers allow it); the workgroup has 4 / QB waves.
 template <int DHP, int QB>
@@ -83,27 +84,42 @@ __global__ __launch_bounds__(64 * (4 / QB), 2) void attention_bf16_kernel(const 
   for (int qb = 0; qb < QB; ++qb) { m[qb] = -INFINITY; l[qb] = 0.f; }
 
   u32x4 rk[Sh::K_PER], rv0[Sh::V_PER], rv1[Sh::V_PER];
-  // global -> registers; rows past the segment end are clamped to its last row (their logits are
-  // masked, the clamped values only need to be finite)
+  // global -> registers.  Each thread's (row, column) inside a tile is fixed, so its byte offsets
+  // are computed once; only a segment's last tile clamps rows past the end to the last row (their
+  // logits are masked, the clamped values only need to be finite).
+  const unsigned char* seg_base = (const unsigned char*)(base + (size_t)w.seg_start * a.ld_qkv);
+  const uint32_t row_bytes = (uint32_t)a.ld_qkv * 2u;
+  int k_key[Sh::K_PER], v_kp[Sh::V_PER];
+  uint32_t k_col[Sh::K_PER], v_col[Sh::V_PER];
+#pragma unroll
+  for (int i = 0; i < Sh::K_PER; ++i) {
+    const int it = tid + i * ANT;
+    k_key[i] = it / Sh::NCH;
+    k_col[i] = (uint32_t)(koff + (it - k_key[i] * Sh::NCH) * 8) * 2u;
+  }
+#pragma unroll
+  for (int i = 0; i < Sh::V_PER; ++i) {
+    const int it = tid + i * ANT;
+    v_kp[i] = it & 31;
+    v_col[i] = (uint32_t)(voff + (it >> 5) * 8) * 2u;
+  }
   auto load_tile = [&](int k0) {
+    const int last = w.seg_len - 1 - k0;  // largest valid row index inside this tile (>= 0)
 #pragma unroll
     for (int i = 0; i < Sh::K_PER; ++i) {
       const int it = tid + i * ANT;
       if (Sh::K_ITEMS % ANT == 0 || it < Sh::K_ITEMS) {
-        const int key = it / Sh::NCH, ch = it - key * Sh::NCH;
-        const int row = min(w.seg_start + k0 + key, seg_end - 1);
-        rk[i] = *(const u32x4*)(base + (size_t)row * a.ld_qkv + koff + ch * 8);
+        const uint32_t row = (uint32_t)(k0 + min(k_key[i], last));
+        rk[i] = *(const u32x4*)(seg_base + (size_t)row * row_bytes + k_col[i]);
       }
     }
 #pragma unroll
     for (int i = 0; i < Sh::V_PER; ++i) {
       const int it = tid + i * ANT;
       if (Sh::V_ITEMS % ANT == 0 || it < Sh::V_ITEMS) {
-        const int ch = it >> 5, kp = it & 31;
-        const int r0 = min(w.seg_start + k0 + 2 * kp, seg_end - 1);
-        const int r1 = min(w.seg_start + k0 + 2 * kp + 1, seg_end - 1);
-        rv0[i] = *(const u32x4*)(base + (size_t)r0 * a.ld_qkv + voff + ch * 8);
-        rv1[i] = *(const u32x4*)(base + (size_t)r1 * a.ld_qkv + voff + ch * 8);
+        const uint32_t r0 = (uint32_t)(k0 + min(2 * v_kp[i], last)), r1 = (uint32_t)(k0 + min(2 * v_kp[i] + 1, last));
+        rv0[i] = *(const u32x4*)(seg_base + (size_t)r0 * row_bytes + v_col[i]);
+        rv1[i] = *(const u32x4*)(seg_base + (size_t)r1 * row_bytes + v_col[i]);
       }
     }
   };
@@ -124,9 +140,9 @@ __global__ __launch_bounds__(64 * (4 / QB), 2) void attention_bf16_kernel(const 
         const int ch = it >> 5, kp = it & 31;
 #pragma unroll
         for (int e = 0; e < 4; ++e) {
-          const uint32_t x0 = rv0[i][e], x1 = rv1[i][e];
-          *(uint32_t*)(sVt + (ch * 8 + 2 * e) * Sh::VT_STRIDE + kp * 4) = (x0 & 0xFFFFu) | (x1 << 16);
-          *(uint32_t*)(sVt + (ch * 8 + 2 * e + 1) * Sh::VT_STRIDE + kp * 4) = (x0 >> 16) | (x1 & 0xFFFF0000u);
+          const uint32_t x0 = rv0[i][e], x1 = rv1[i][e];  // v_perm_b32: bytes 0-3 = x0, 4-7 = x1
+          *(uint32_t*)(sVt + (ch * 8 + 2 * e) * Sh::VT_STRIDE + kp * 4) = __builtin_amdgcn_perm(x1, x0, 0x05040100u);
+          *(uint32_t*)(sVt + (ch * 8 + 2 * e + 1) * Sh::VT_STRIDE + kp * 4) = __builtin_amdgcn_perm(x1, x0, 0x07060302u);
         }
       }
     }
@@ -177,16 +193,19 @@ __global__ __launch_bounds__(64 * (4 / QB), 2) void attention_bf16_kernel(const 
 #pragma unroll
         for (int v = 1; v < 16; ++v) mx = fmaxf(mx, st[qb][v]);
         mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
-        const float m_new = fmaxf(m[qb], mx * scale_log2);
-        // rescale the output accumulator only if some query's maximum moved
-        if (__builtin_amdgcn_ballot_w64(m_new != m[qb]) != 0) {
-          const float corr = __builtin_amdgcn_exp2f(m[qb] - m_new);
+        // The reference maximum m only has to keep exp2 in range, not to be the exact running
+        // maximum: it moves (and the accumulators are rescaled) only when some query's logits
+        // outgrow it by more than 2^RESCALE_SLACK, so p <= 2^RESCALE_SLACK instead of p <= 1.
+        const float m_new = mx * scale_log2;
+        if (__builtin_amdgcn_ballot_w64(m_new > m[qb] + RESCALE_SLACK) != 0) {
+          const float m_up = fmaxf(m[qb], m_new);
+          const float corr = __builtin_amdgcn_exp2f(m[qb] - m_up);
           l[qb] *= corr;
 #pragma unroll
           for (int b = 0; b < Sh::DB; ++b)
 #pragma unroll
             for (int v = 0; v < 16; ++v) o[qb][b][v] *= corr;
-          m[qb] = m_new;
+          m[qb] = m_up;
         }
         const float neg_m = -m[qb];
         float psum = 0.f;
