@@ -70,6 +70,8 @@ def main():
     ap.add_argument("--workload", default="cfg3", choices=["cfg1", "cfg2", "cfg3", "cfg4", "cfg5"])
     ap.add_argument("--cpu-sample", type=int, default=4, help="images the CPU oracle encodes (0 = skip)")
     ap.add_argument("--no-kernel-events", action="store_true", help="time the steps without per-kernel events")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="run five plain 1 GiB device copies and exit (scale reference for rocprofv3 FETCH_SIZE / WRITE_SIZE)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU (no sharding, no collectives); --gpus must be 1", file=sys.stderr)
@@ -83,6 +85,14 @@ def main():
     if not torch.cuda.is_available():
         print("bench.py: no HIP device visible; there is no CPU path", file=sys.stderr)
         sys.exit(2)
+    if args.copy_calibration:
+        src = torch.empty(1 << 30, dtype=torch.uint8, device="cuda").fill_(1)
+        dst = torch.empty_like(src)
+        for _ in range(5):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        print(json.dumps({"copy_calibration": {"bytes_read": 1 << 30, "bytes_written": 1 << 30, "copies": 5}}))
+        return
     cfg, ipr, to = gen.make_workload(args.workload)
     n_images, n_tiles = int(ipr.sum()), int(to[-1])
     T = gen.tokens_per_tile(cfg)

@@ -53,7 +53,13 @@ __global__ __launch_bounds__(64 * (4 / QB), 2) void attention_bf16_kernel(const 
   constexpr int ANT = Sh::ANT;
   extern __shared__ __attribute__((aligned(16))) unsigned char lds[];  // 2 stages of (K tile, V^T tile)
 
-  const AttnWork w = a.work[blockIdx.x];
+  // Workgroup ids are dealt round-robin to the 8 XCDs.  Consecutive work items are the query
+  // blocks of one segment, which read the same K and V rows: give each XCD a contiguous run of
+  // work items so those rows are fetched into one L2 only.
+  const int per_xcd = (a.n_work + 7) >> 3;
+  const int wi = (blockIdx.x & 7) * per_xcd + (blockIdx.x >> 3);
+  if (wi >= a.n_work) return;
+  const AttnWork w = a.work[wi];
   const int head = blockIdx.y;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int lq = lane & 31, g = lane >> 5;
@@ -277,7 +283,7 @@ hipError_t launch_attention_bf16(const AttnArgs& a, hipStream_t s) {
   if (a.n_work <= 0) return hipSuccess;
   if (a.ld_qkv % 8 != 0 || a.ld_o % 4 != 0) return hipErrorInvalidValue;
   const float scale_log2 = 1.4426950408889634f / sqrtf((float)a.dh);
-  const dim3 grid(a.n_work, a.heads);
+  const dim3 grid(((a.n_work + 7) / 8) * 8, a.heads);
 #define VIT_ATTN(DHP, QB)                                                                              \
   do {                                                                                                 \
     constexpr int smem = 2 * AttnShape<DHP, QB>::STAGE;                                                \
