@@ -48,6 +48,9 @@ CONFIGS = {
     "test_dh72_bf16": _cfg(60, 14, 144, 2, 272, 2, has_cls=0, proj_dims=(96,)),
     # head dim 80, CLS, local + global layers, no projector, no final LN
     "test_dh80_bf16": _cfg(70, 14, 160, 2, 320, 1, layers_global=2, final_ln=0),
+    # head dims 96 and 128 (the remaining attention instantiations)
+    "test_dh96_bf16": _cfg(56, 14, 192, 2, 384, 1, layers_global=1, proj_dims=(64,)),
+    "test_dh128_bf16": _cfg(56, 14, 256, 2, 512, 2, has_cls=0),
     # several key tiles per segment and a ragged tail: 15x15 + 1 = 226 tokens per tile
     "test_medium_bf16": _cfg(210, 14, 256, 4, 512, 2, layers_global=1, proj_dims=(256, 128)),
     "test_medium_fp32": _cfg(210, 14, 256, 4, 512, 2, layers_global=1, proj_dims=(256, 128), dtype="fp32"),

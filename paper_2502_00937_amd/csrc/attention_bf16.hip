@@ -59,7 +59,7 @@ __global__ __launch_bounds__(64 * (4 / QB), 2) void attention_bf16_kernel(const 
   const int per_xcd = (a.n_work + 7) >> 3;
   const int wi = (blockIdx.x & 7) * per_xcd + (blockIdx.x >> 3);
   if (wi >= a.n_work) return;
-  const AttnWork w = a.work[wi];
+  const AttnWork w = a.work[a.reverse ? a.n_work - 1 - wi : wi];
   const int head = blockIdx.y;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int lq = lane & 31, g = lane >> 5;

@@ -94,6 +94,7 @@ struct GemmArgs {
   int tokens;         // EPI_PATCH: tokens per tile T
   int cls;            // EPI_PATCH: 1 if a CLS row precedes the patches
   int epilogue;
+  int reverse;        // 1: walk the row blocks from the last to the first (see vit_encode_packed)
 };
 
 // Applies one epilogue to a single accumulator; the caller guarantees row < M and col < N.
@@ -130,6 +131,7 @@ struct AttnArgs {
   int dh;      // true head dim (for the logit scale)
   int dh_pad;  // padded head dim used in memory
   int ld_qkv, ld_o;
+  int reverse;  // 1: walk the work list from the last item to the first
 };
 
 // ---- launchers (defined in the .hip files) ----------------------------------------------
@@ -141,7 +143,7 @@ hipError_t launch_gemm_f32(const GemmArgs& a, hipStream_t s);
 hipError_t launch_attention_f32(const AttnArgs& a, hipStream_t s);
 // shared, templated on activation type inside
 hipError_t launch_layernorm(const float* x, int ldx, void* out, int ldo, int out_cols, const float* gamma,
-                            const float* beta, float eps, int rows, int D, int normalize, int out_bf16,
+                            const float* beta, float eps, int rows, int D, int normalize, int out_bf16, int reverse,
                             hipStream_t s);
 hipError_t launch_patch_gather(const float* pixels, void* patches, int ld, int n_tiles, int C, int S, int p, int g,
                                int Kpad, int out_bf16, hipStream_t s);

@@ -394,7 +394,9 @@ __global__ __launch_bounds__(512) void gemm_bf16_dma_kernel(const GemmArgs a, in
     const int mblk = g / n_bands, band = g - mblk * n_bands;
     tm = mblk * D_GROUP_M + sm;
     tn = band * D_GROUP_N + sn;
-    return tm < tiles_m && tn < tiles_n;
+    const bool ok = tm < tiles_m && tn < tiles_n;
+    if (a.reverse) tm = tiles_m - 1 - tm;
+    return ok;
   };
   auto next_group = [&](int g) {  // first group >= g (stride 8) in which this slot has a tile, or n_groups
     int tm, tn;
@@ -655,13 +657,9 @@ hipError_t launch_gemm_bf16(const GemmArgs& a, hipStream_t s) {
   // 16-byte epilogue accesses need 8-element aligned columns and leading dimensions
   if (a.K <= 0 || a.K % BK != 0 || a.lda % 8 != 0 || a.ldw % 8 != 0 || a.ldo % 8 != 0 || a.N % 8 != 0)
     return hipErrorInvalidValue;
-  // Large tiles need enough of them to fill 256 compute units.
+  // The persistent 256 x 256 kernel wants at least one tile per compute unit.
   const long big_tiles = (long)((a.M + 255) / 256) * ((a.N + 255) / 256);
-#ifdef VIT_GEMM_NO_DMA
-  if (big_tiles >= 512) return launch_cfg<256, 256, 2, 4>(a, s);
-#else
-  if (big_tiles >= 512) return launch_dma(a, s);
-#endif
+  if (big_tiles >= 256) return launch_dma(a, s);
   return launch_cfg<128, 128, 2, 2>(a, s);
 }
 

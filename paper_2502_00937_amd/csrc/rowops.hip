@@ -20,10 +20,12 @@ __device__ inline float wave_sum(float v) {
 template <typename OutT, int MAXV, int NORMALIZE>
 __global__ __launch_bounds__(256) void layernorm_kernel(const float* __restrict__ x, int ldx, OutT* __restrict__ out,
                                                         int ldo, int out_cols, const float* __restrict__ gamma,
-                                                        const float* __restrict__ beta, float eps, int rows, int D) {
+                                                        const float* __restrict__ beta, float eps, int rows, int D,
+                                                        int reverse) {
   const int lane = threadIdx.x & 63;
-  const int row = blockIdx.x * 4 + (threadIdx.x >> 6);
+  int row = blockIdx.x * 4 + (threadIdx.x >> 6);
   if (row >= rows) return;
+  if (reverse) row = rows - 1 - row;
   const float* xr = x + (size_t)row * ldx;
   f32x4 v[MAXV];
   float s = 0.f;
@@ -119,12 +121,12 @@ __global__ __launch_bounds__(256) void fill_zero_cols_kernel(T* buf, int ld, lon
 
 template <typename OutT, int NORMALIZE>
 hipError_t ln_dispatch(const float* x, int ldx, void* out, int ldo, int out_cols, const float* gamma, const float* beta,
-                       float eps, int rows, int D, hipStream_t s) {
+                       float eps, int rows, int D, int reverse, hipStream_t s) {
   const dim3 grid((rows + 3) / 4), block(256);
   const int need = (out_cols + 255) / 256;  // float4 slots per lane
 #define VIT_LN(MAXV)                                                                                              \
   hipLaunchKernelGGL((layernorm_kernel<OutT, MAXV, NORMALIZE>), grid, block, 0, s, x, ldx, (OutT*)out, ldo, out_cols, \
-                     gamma, beta, eps, rows, D)
+                     gamma, beta, eps, rows, D, reverse)
   if (need <= 1) VIT_LN(1);
   else if (need <= 2) VIT_LN(2);
   else if (need <= 4) VIT_LN(4);
@@ -139,16 +141,16 @@ hipError_t ln_dispatch(const float* x, int ldx, void* out, int ldo, int out_cols
 }  // namespace
 
 hipError_t launch_layernorm(const float* x, int ldx, void* out, int ldo, int out_cols, const float* gamma,
-                            const float* beta, float eps, int rows, int D, int normalize, int out_bf16,
+                            const float* beta, float eps, int rows, int D, int normalize, int out_bf16, int reverse,
                             hipStream_t s) {
   if (rows <= 0) return hipSuccess;
   if (D % 4 != 0 || out_cols % 4 != 0 || ldx % 4 != 0 || ldo % 4 != 0 || out_cols < D) return hipErrorInvalidValue;
   if (out_bf16) {
-    return normalize ? ln_dispatch<bf16_t, 1>(x, ldx, out, ldo, out_cols, gamma, beta, eps, rows, D, s)
-                     : ln_dispatch<bf16_t, 0>(x, ldx, out, ldo, out_cols, gamma, beta, eps, rows, D, s);
+    return normalize ? ln_dispatch<bf16_t, 1>(x, ldx, out, ldo, out_cols, gamma, beta, eps, rows, D, reverse, s)
+                     : ln_dispatch<bf16_t, 0>(x, ldx, out, ldo, out_cols, gamma, beta, eps, rows, D, reverse, s);
   }
-  return normalize ? ln_dispatch<float, 1>(x, ldx, out, ldo, out_cols, gamma, beta, eps, rows, D, s)
-                   : ln_dispatch<float, 0>(x, ldx, out, ldo, out_cols, gamma, beta, eps, rows, D, s);
+  return normalize ? ln_dispatch<float, 1>(x, ldx, out, ldo, out_cols, gamma, beta, eps, rows, D, reverse, s)
+                   : ln_dispatch<float, 0>(x, ldx, out, ldo, out_cols, gamma, beta, eps, rows, D, reverse, s);
 }
 
 hipError_t launch_patch_gather(const float* pixels, void* patches, int ld, int n_tiles, int C, int S, int p, int g,

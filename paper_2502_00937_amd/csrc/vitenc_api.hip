@@ -485,18 +485,25 @@ vit_status_t vit_encode_packed(vit_encoder_t* e, const float* pixels, const int3
     slot.used = true;
   }
 
+  // Every kernel of the chain walks the token rows in the direction opposite to its producer:
+  // what a kernel wrote last is still in the 256 MB memory-side cache when its consumer starts there.
+  int reverse = 0;
   auto gemm = [&](const Linear& lin, const void* A, int lda, int M, int epi, void* out, int ldo, float* resid) -> hipError_t {
     GemmArgs a;
     memset(&a, 0, sizeof(a));
     a.A = A; a.W = lin.W; a.bias = lin.bias; a.out = out; a.resid = resid; a.pos = e->pos;
     a.M = M; a.N = lin.N; a.K = lin.K; a.lda = lda; a.ldw = lin.K; a.ldo = ldo;
     a.patches = d.P; a.tokens = d.T; a.cls = d.has_cls; a.epilogue = epi;
+    a.reverse = reverse;
+    reverse ^= 1;
     ProfScope ps(e, s, VIT_PROF_GEMM);
     return d.bf16 ? launch_gemm_bf16(a, s) : launch_gemm_f32(a, s);
   };
   auto layernorm = [&](const float* g_, const float* b_, int normalize, void* out, int ldo, int out_cols) -> hipError_t {
     ProfScope ps(e, s, VIT_PROF_LAYERNORM);
-    return launch_layernorm(x, d.D, out, ldo, out_cols, g_, b_, d.eps, n_tok, d.D, normalize, d.bf16, s);
+    const int rev = reverse;
+    reverse ^= 1;
+    return launch_layernorm(x, d.D, out, ldo, out_cols, g_, b_, d.eps, n_tok, d.D, normalize, d.bf16, rev, s);
   };
 
   // ---- patch embedding: gather -> matrix product with (+bias, +pos, row remap) epilogue; CLS rows
@@ -520,6 +527,8 @@ vit_status_t vit_encode_packed(vit_encoder_t* e, const float* pixels, const int3
       a.work = global ? tables + w.max_work : tables;
       a.n_work = global ? n_global : n_local;
       a.heads = d.H; a.dh = d.dh; a.dh_pad = d.dhp; a.ld_qkv = d.QKVN; a.ld_o = d.Op;
+      a.reverse = reverse;
+      reverse ^= 1;
       ProfScope ps(e, s, VIT_PROF_ATTENTION);
       HIP_TRY(d.bf16 ? launch_attention_bf16(a, s) : launch_attention_f32(a, s));
     }

@@ -15,6 +15,8 @@ pytestmark = pytest.mark.gpu
     ("test_dh80_bf16", [3, 1], [1, 1]),
     ("test_medium_fp32", [2, 1], [2]),
     ("test_medium_bf16", [2, 1, 4], [1, 1, 1]),
+    ("test_dh96_bf16", [2, 1, 3], [2, 1]),
+    ("test_dh128_bf16", [1, 2, 1], [1, 2]),
 ])
 def test_small_configs_match_oracle(name, tpi, ipr):
     say(f"case {name} tiles_per_image={tpi} images_per_request={ipr}")
@@ -38,6 +40,17 @@ def test_ragged_many_tiles_bf16():
     tpi = [1, 5, 1, 1, 2, 7, 1, 3]                     # 21 tiles -> 4746 rows
     say("case ragged 21 tiles")
     check_case(cfg, tpi, [1, 0, 4, 3], label="ragged")
+
+
+def test_wide_batch_reaches_persistent_gemm():
+    """Enough token rows (160 tiles x 226 = 36 160) that every matrix product of this small network takes the
+    persistent 256 x 256 kernel, including a ragged last row block, K of 4 and 8 k-stages and a column band
+    that is narrower than a tile group.  The oracle encodes sampled images (first, a multi-tile one, last)."""
+    cfg = gen.get_config("test_medium_bf16")
+    tpi = [1, 4, 1, 1, 2, 7, 1, 3] * 8           # 64 images, 160 tiles
+    say("case wide batch (160 tiles, persistent GEMM)")
+    got, _ = check_case(cfg, tpi, [len(tpi)], images=[0, 5, 63], label="wide")
+    assert got.shape[0] == 160 * 226
 
 
 def test_packing_invariance_on_gpu():

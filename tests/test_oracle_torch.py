@@ -72,6 +72,8 @@ CASES = [
     ("test_dh80_bf16", [3, 1]),
     ("test_medium_fp32", [2]),
     ("cfg1_tiny_fp32", [1, 1]),
+    ("test_dh96_bf16", [2, 1]),
+    ("test_dh128_bf16", [1, 2]),
 ]
 
 
