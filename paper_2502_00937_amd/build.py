@@ -14,7 +14,7 @@ SOURCES = ["vitenc_api.hip", "gemm_bf16.hip", "attention_bf16.hip", "rowops.hip"
 FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-fvisibility=hidden",
     "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
-    "-Wno-unused-result",
+    "-Wno-unused-result", "-Wno-inline-asm",
 ]
 
 

@@ -338,6 +338,7 @@ __device__ __forceinline__ void wave_epilogue_p(const GemmArgs& a, f32x16 (&acc)
       }
     }
   } else {  // EPI_BIAS, EPI_BIAS_GELU: bf16 output, pieces of 16 rows x 64 columns (128 bytes + pad)
+    // (storing the 8-byte register quads directly was measured slower than this LDS round trip)
 #pragma unroll
     for (int i = 0; i < FM; ++i) {
       u32x2 pk[FN][4];  // all lanes convert once; the two half-wave passes below only move data
@@ -423,14 +424,20 @@ __global__ __launch_bounds__(512) void gemm_bf16_dma_kernel(const GemmArgs a, in
   };
   set_load_tile();
   // one direct-to-LDS instruction of ring slot `st` at the load cursor: i in [0,2) -> A rows, [2,4) -> W rows
+  // The instruction is written as inline assembly so that the compiler's wait-count insertion, which
+  // cannot know that the ring slot written here is never one being read, does not fence every
+  // surrounding LDS read; completion is tracked by hand (sync_stage).  M0 holds the LDS base.
+  auto dma16 = [&](const unsigned char* gptr, unsigned char* lptr) {
+    // low 32 bits of a generic LDS pointer = LDS offset; wave-uniform by construction
+    const uint32_t lds_addr = __builtin_amdgcn_readfirstlane((uint32_t)(uintptr_t)lptr);
+    asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, off" ::"s"(lds_addr), "v"(gptr) : "memory", "m0");
+  };
   auto issue_load = [&](int st, int i) {
     unsigned char* base = smem + st * D_STAGE_BYTES;
     if (i < 2)
-      __builtin_amdgcn_global_load_lds((gptr_t)(baseA + i * a_step + kt_l * (D_BK * 2) + offA),
-                                       (lptr_t)(base + (wave * 32 + i * 16) * 64), 16, 0, 0);
+      dma16(baseA + i * a_step + kt_l * (D_BK * 2) + offA, base + (wave * 32 + i * 16) * 64);
     else
-      __builtin_amdgcn_global_load_lds((gptr_t)(baseW + (i - 2) * w_step + kt_l * (D_BK * 2) + offW),
-                                       (lptr_t)(base + D_BM * 64 + (wave * 32 + (i - 2) * 16) * 64), 16, 0, 0);
+      dma16(baseW + (i - 2) * w_step + kt_l * (D_BK * 2) + offW, base + D_BM * 64 + (wave * 32 + (i - 2) * 16) * 64);
   };
   const int KT = a.K / D_BK;
   auto advance_load_cursor = [&]() {
