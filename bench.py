@@ -23,6 +23,10 @@ import numpy as np  # noqa: E402
 
 PEAK_BF16_TFLOPS = 2500.0  # MI355X dense bf16 MFMA peak
 HBM_PEAK_GBS = 8000.0
+# HBM-side bytes of all matrix-product launches of ONE cfg3 step, from the two rocprofv3 --pmc runs
+# (FETCH_SIZE x 2.0 + WRITE_SIZE x 1.0, factors from the copy calibration) summarised in
+# profiles/kernels_cfg3_ragged_hbm_traffic.md.  A profile figure, not measured by this script.
+GEMM_TRAFFIC_BYTES_PER_STEP = {"cfg3": 257.3e9}
 
 
 def flops(cfg, tile_offsets):
@@ -147,7 +151,8 @@ def main():
         result["roofline"] = {
             "bound": "mfma", "kernel": "gemm_bf16_kernel (all matrix products of one step)",
             "achieved": achieved, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": achieved / PEAK_BF16_TFLOPS,
-            "traffic": None, "launches_per_step": int(gemm_n), "ms_per_step": gemm_ms,
+            "traffic": GEMM_TRAFFIC_BYTES_PER_STEP.get(args.workload), "traffic_unit": "bytes per step (all launches), rocprofv3 --pmc",
+            "launches_per_step": int(gemm_n), "ms_per_step": gemm_ms,
             "avg_launch_ms": gemm_ms / max(gemm_n, 1), "flop_per_step": gemm_f,
         }
         result["kernel_ms_per_step"] = fam_ms
