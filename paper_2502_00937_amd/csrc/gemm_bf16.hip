@@ -247,7 +247,7 @@ __global__ __launch_bounds__(WM* WN * 64) void gemm_bf16_kernel(const GemmArgs a
 // * The loads of a step are spread between its MFMAs: a wave that issued them back to back would
 //   sit in the memory pipeline's back-pressure while the matrix core runs dry.
 // * Tile order: the tile grid is cut into (8-row-block x 4-column-band) groups of 32 tiles, one per
-//   compute unit of an XCD; consecutive groups along N go to consecutive XCDs, so the XCDs working
+//   compute unit of an XCD (a remainder of one or two tile columns is cut into 32 x 1 or 16 x 2 groups); consecutive groups along N go to consecutive XCDs, so the XCDs working
 //   at the same time share A rows (first fetch fills the memory-side cache for the others) and the
 //   32 units of one XCD share both operands in its L2.
 // * Epilogue staging has its own 18 KiB of LDS (16 rows x 144 bytes per wave).
@@ -379,7 +379,7 @@ __device__ __forceinline__ void wave_epilogue_p(const GemmArgs& a, f32x16 (&acc)
 
 template <int EPI>
 __global__ __launch_bounds__(512) void gemm_bf16_dma_kernel(const GemmArgs a, int tiles_m, int tiles_n, int n_bands,
-                                                            int n_groups) {
+                                                            int groups_full, int narrow_w, int n_groups) {
   constexpr int FM = 4, FN = 2, TM = 128, TN = 64;
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
   unsigned char* staging = smem + D_ST * D_STAGE_BYTES;
@@ -392,9 +392,14 @@ __global__ __launch_bounds__(512) void gemm_bf16_dma_kernel(const GemmArgs a, in
   const int xcd = blockIdx.x & 7, slot = blockIdx.x >> 3;  // slot in [0, 32)
   const int sm = slot / D_GROUP_N, sn = slot % D_GROUP_N;
   auto tile_of = [&](int g, int& tm, int& tn) {  // false when the slot has no tile in group g
-    const int mblk = g / n_bands, band = g - mblk * n_bands;
-    tm = mblk * D_GROUP_M + sm;
-    tn = band * D_GROUP_N + sn;
+    if (g < groups_full) {  // 8 x 4 groups over the full-width column bands
+      const int mblk = g / n_bands, band = g - mblk * n_bands;
+      tm = mblk * D_GROUP_M + sm;
+      tn = band * D_GROUP_N + sn;
+    } else {  // the last one or two tile columns: 32 x 1 or 16 x 2 groups, so no slot idles
+      tm = (g - groups_full) * (32 / narrow_w) + slot / narrow_w;
+      tn = n_bands * D_GROUP_N + slot % narrow_w;
+    }
     const bool ok = tm < tiles_m && tn < tiles_n;
     if (a.reverse) tm = tiles_m - 1 - tm;
     return ok;
@@ -587,9 +592,14 @@ __global__ __launch_bounds__(512) void gemm_bf16_dma_kernel(const GemmArgs a, in
 
 hipError_t launch_dma(const GemmArgs& a, hipStream_t s) {
   const int tiles_m = (a.M + D_BM - 1) / D_BM, tiles_n = (a.N + D_BN - 1) / D_BN;
-  const int n_bands = (tiles_n + D_GROUP_N - 1) / D_GROUP_N;
-  const int m_blocks = (tiles_m + D_GROUP_M - 1) / D_GROUP_M;
-  const int n_groups = m_blocks * n_bands;
+  // column bands of four tiles; a remainder of one or two tile columns gets its own group shape
+  // (a remainder of three is a band with one idle column)
+  const int rem = tiles_n % D_GROUP_N;
+  const int narrow_w = rem == 3 ? 0 : rem;
+  const int n_bands = tiles_n / D_GROUP_N + (rem == 3 ? 1 : 0);
+  const int groups_full = ((tiles_m + D_GROUP_M - 1) / D_GROUP_M) * n_bands;
+  const int groups_narrow = narrow_w ? (tiles_m + 32 / narrow_w - 1) / (32 / narrow_w) : 0;
+  const int n_groups = groups_full + groups_narrow;
   static int n_cu = 0;
   if (n_cu == 0) {
     int dev = 0;
@@ -610,7 +620,8 @@ hipError_t launch_dma(const GemmArgs& a, hipStream_t s) {
       if (e != hipSuccess) return e;                                                                                 \
       attr_set = true;                                                                                               \
     }                                                                                                                \
-    hipLaunchKernelGGL(kfn, dim3(grid), dim3(512), D_LDS_BYTES, s, a, tiles_m, tiles_n, n_bands, n_groups);          \
+    hipLaunchKernelGGL(kfn, dim3(grid), dim3(512), D_LDS_BYTES, s, a, tiles_m, tiles_n, n_bands, groups_full,        \
+                       narrow_w, n_groups);                                                                          \
   } while (0)
   switch (a.epilogue) {
     case EPI_BIAS: VIT_LAUNCH(EPI_BIAS); break;
