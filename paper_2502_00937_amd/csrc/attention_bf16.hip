@@ -1,4 +1,4 @@
-// Variable-length flash attention on bf16 MFMA.  A work item is a block of 128 query rows of
+// Variable-length flash attention on bf16 MFMA.  A work item is a block of 128 or 256 query rows of
 // one segment (a tile, or all tiles of an image); keys never come from outside the segment, so
 // no padding or masking crosses images.
 //
@@ -26,14 +26,16 @@ namespace vitenc {
 
 namespace {
 
-constexpr int AQ = 128;  // query rows per workgroup
 constexpr int AKV = 64;  // keys per LDS tile
 constexpr float RESCALE_SLACK = 8.0f;  // log2 units the logits may exceed the reference maximum by
 
-// QB = 32-query blocks per wave (2 where the registers allow it); the workgroup has 4 / QB waves.
-template <int DHP, int QB>
+// QB = 32-query blocks per wave, NW = waves per workgroup: a work item is 32 * QB * NW query rows.
+// Head dim 64 runs 2 x 2 (128 rows); the wider heads run 2 x 4 (256 rows), where the K/V staging
+// registers per thread halve and the 64-query wave still fits the register file.
+template <int DHP, int QB, int NW>
 struct AttnShape {
-  static constexpr int ANT = 64 * (4 / QB);      // threads per workgroup
+  static constexpr int ANT = 64 * NW;            // threads per workgroup
+  static constexpr int AQ = 32 * QB * NW;        // query rows per work item
   static constexpr int KS = DHP / 16;            // k-steps of the S^T product
   static constexpr int DB = (DHP + 31) / 32;     // 32-row blocks of O^T
   static constexpr int NCH = DHP / 8;            // 16-byte chunks per K/V row
@@ -47,9 +49,9 @@ struct AttnShape {
   static constexpr int K_PER = (K_ITEMS + ANT - 1) / ANT, V_PER = (V_ITEMS + ANT - 1) / ANT;
 };
 
-template <int DHP, int QB>
-__global__ __launch_bounds__(64 * (4 / QB), 2) void attention_bf16_kernel(const AttnArgs a, float scale_log2) {
-  using Sh = AttnShape<DHP, QB>;
+template <int DHP, int QB, int NW>
+__global__ __launch_bounds__(64 * NW, 2) void attention_bf16_kernel(const AttnArgs a, float scale_log2) {
+  using Sh = AttnShape<DHP, QB, NW>;
   constexpr int ANT = Sh::ANT;
   extern __shared__ __attribute__((aligned(16))) unsigned char lds[];  // 2 stages of (K tile, V^T tile)
 
@@ -277,30 +279,30 @@ __global__ __launch_bounds__(64 * (4 / QB), 2) void attention_bf16_kernel(const 
 
 }  // namespace
 
-int attention_q_block(int dtype_bf16) { return dtype_bf16 ? AQ : 64; }
+int attention_q_block(int dtype_bf16, int dh_pad) { return !dtype_bf16 ? 64 : dh_pad == 64 ? 128 : 256; }
 
 hipError_t launch_attention_bf16(const AttnArgs& a, hipStream_t s) {
   if (a.n_work <= 0) return hipSuccess;
   if (a.ld_qkv % 8 != 0 || a.ld_o % 4 != 0) return hipErrorInvalidValue;
   const float scale_log2 = 1.4426950408889634f / sqrtf((float)a.dh);
   const dim3 grid(((a.n_work + 7) / 8) * 8, a.heads);
-#define VIT_ATTN(DHP, QB)                                                                              \
+#define VIT_ATTN(DHP, QB, NW)                                                                            \
   do {                                                                                                 \
-    constexpr int smem = 2 * AttnShape<DHP, QB>::STAGE;                                                \
-    auto kfn = attention_bf16_kernel<DHP, QB>;                                                         \
+    constexpr int smem = 2 * AttnShape<DHP, QB, NW>::STAGE;                                            \
+    auto kfn = attention_bf16_kernel<DHP, QB, NW>;                                                     \
     static bool attr_set = false; /* the dynamic LDS limit is raised once per kernel */                \
     if (!attr_set) {                                                                                   \
       hipError_t e = hipFuncSetAttribute((const void*)kfn, hipFuncAttributeMaxDynamicSharedMemorySize, smem); \
       if (e != hipSuccess) return e;                                                                   \
       attr_set = true;                                                                                 \
     }                                                                                                  \
-    hipLaunchKernelGGL(kfn, grid, dim3(AttnShape<DHP, QB>::ANT), smem, s, a, scale_log2);              \
+    hipLaunchKernelGGL(kfn, grid, dim3(AttnShape<DHP, QB, NW>::ANT), smem, s, a, scale_log2);          \
   } while (0)
   switch (a.dh_pad) {
-    case 64: VIT_ATTN(64, 2); break;
-    case 80: VIT_ATTN(80, 1); break;
-    case 96: VIT_ATTN(96, 1); break;
-    case 128: VIT_ATTN(128, 1); break;
+    case 64: VIT_ATTN(64, 2, 2); break;
+    case 80: VIT_ATTN(80, 2, 4); break;
+    case 96: VIT_ATTN(96, 2, 4); break;
+    case 128: VIT_ATTN(128, 1, 8); break;
     default: return hipErrorInvalidValue;
   }
 #undef VIT_ATTN

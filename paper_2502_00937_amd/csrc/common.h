@@ -151,7 +151,7 @@ hipError_t launch_cls_rows(float* x, int ldx, const float* cls, const float* pos
                            hipStream_t s);
 hipError_t launch_fill_zero_cols(void* buf, int ld, int rows, int col0, int col1, int elem_bytes, hipStream_t s);
 
-int attention_q_block(int dtype_bf16);  // query rows per work item for each path
+int attention_q_block(int dtype_bf16, int dh_pad);  // query rows per work item for each path and head dim
 int gemm_row_pad();                     // row padding every activation buffer must have
 
 }  // namespace vitenc

@@ -232,31 +232,40 @@ __global__ __launch_bounds__(WM* WN * 64) void gemm_bf16_kernel(const GemmArgs a
 // ---------------------------------------------------------------------------------------------
 // Large-problem kernel: persistent, 256 x 256 tile, eight waves (two per SIMD), 128 x 64 per wave.
 //
-// The memory system, not the matrix cores, sets the pace of this product on gfx950: what a compute
-// unit can pull through its L1 is about 100 GB/s, and a 256 x 256 tile needs half of that at full
-// MFMA rate, a 256 x 128 tile three quarters.  Hence the biggest tile the accumulators allow.
+// The memory system, not the matrix cores, sets the pace of this product on gfx950.  A compute
+// unit's L1 is filled in whole 128-byte lines: a probe that reads L2-resident rows in 64-byte
+// pieces gets 70 GB/s per unit, in 128-byte pieces 135 GB/s.  A 256 x 256 tile needs 32 KiB per
+// 32 k-values, which at full MFMA rate is 60 GB/s: affordable only when every line is asked for
+// once.  Hence 64-wide k-stages (one 128-byte line per row) and the biggest tile the accumulators
+// allow.
 //
 // * One workgroup per compute unit walks a list of tiles.  Operand tiles go global -> LDS directly
-//   (global_load_lds_dwordx4: each lane supplies its own global address, the wave writes 1 KiB of
-//   consecutive LDS) through a ring of four 32-wide k-stages.  The ring runs three steps ahead of
-//   the multiplication and does not stop at tile boundaries, so the next tile's first stages land
-//   while the current tile finishes and its epilogue runs; no launch gap, no cold prologue per tile.
-// * LDS rows are 64 bytes; the 16-byte chunk index is XORed with (row >> 2) & 3, which the lane
+//   (global_load_lds_dwordx4: each lane supplies its own global offset, the wave writes 1 KiB of
+//   consecutive LDS = 8 rows) through two 64-wide k-stages of 64 KiB.  The stream of stages does
+//   not stop at tile boundaries, so the next tile's first stages land while the current tile
+//   finishes and its epilogue runs; no launch gap, no cold prologue per tile.
+// * A stage is multiplied in four 16-wide sub-steps, each reading the next sub-step's fragments
+//   while its own MFMAs run.  Before the last sub-step one wait + barrier establishes both that
+//   the other stage has landed and that nobody reads this stage's LDS any more; the last sub-step
+//   then reads the other stage's first fragments and issues the loads that refill this stage, one
+//   after each MFMA (a wave that issued them back to back would sit in the memory pipeline's
+//   back-pressure while the matrix core runs dry).
+// * LDS rows are 128 bytes; the 16-byte chunk index is XORed with (row >> 1) & 7, which the lane
 //   achieves by choosing which global chunk it loads, so any 16 consecutive rows of one logical
 //   chunk fall on 16 distinct 16-byte bank groups of the 64 banks.
-// * The loads of a step are spread between its MFMAs: a wave that issued them back to back would
-//   sit in the memory pipeline's back-pressure while the matrix core runs dry.
 // * Tile order: the tile grid is cut into (8-row-block x 4-column-band) groups of 32 tiles, one per
-//   compute unit of an XCD (a remainder of one or two tile columns is cut into 32 x 1 or 16 x 2 groups); consecutive groups along N go to consecutive XCDs, so the XCDs working
-//   at the same time share A rows (first fetch fills the memory-side cache for the others) and the
-//   32 units of one XCD share both operands in its L2.
+//   compute unit of an XCD (a remainder of one or two tile columns is cut into 32 x 1 or 16 x 2
+//   groups); consecutive groups along N go to consecutive XCDs, so the XCDs working at the same
+//   time share A rows (first fetch fills the memory-side cache for the others) and the 32 units of
+//   one XCD share both operands in its L2.
 // * Epilogue staging has its own 18 KiB of LDS (16 rows x 144 bytes per wave).
-constexpr int D_BM = 256, D_BN = 256, D_BK = 32, D_ST = 4;
-constexpr int D_STAGE_BYTES = (D_BM + D_BN) * D_BK * 2;  // 32 KiB
+constexpr int D_BM = 256, D_BN = 256, D_BK = 64, D_ST = 2;
+constexpr int D_ROW = D_BK * 2;                       // bytes per LDS row
+constexpr int D_STAGE_BYTES = (D_BM + D_BN) * D_ROW;  // 64 KiB
 constexpr int D_STAGING_ROW = 144, D_STAGING_BYTES = 8 * 16 * D_STAGING_ROW;
 constexpr int D_LDS_BYTES = D_ST * D_STAGE_BYTES + D_STAGING_BYTES;  // 146 KiB of the 160 KiB
 constexpr int D_GROUP_M = 8, D_GROUP_N = 4;
-constexpr int D_LOADS = 4;  // direct-to-LDS instructions per wave and stage (2 for A, 2 for W)
+constexpr int D_LOADS = 8;  // direct-to-LDS instructions per wave and stage (4 for A, 4 for W), 8 rows each
 
 typedef const __attribute__((address_space(1))) void* gptr_t;
 typedef __attribute__((address_space(3))) void* lptr_t;
@@ -384,7 +393,8 @@ __global__ __launch_bounds__(512) void gemm_bf16_dma_kernel(const GemmArgs a, in
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
   unsigned char* staging = smem + D_ST * D_STAGE_BYTES;
 
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);  // wave-uniform: keeps addresses in scalar registers
   const int wm = wave >> 2, wn = wave & 3;
   const int lrow = lane & 31, lk = lane >> 5;
 
@@ -410,14 +420,18 @@ __global__ __launch_bounds__(512) void gemm_bf16_dma_kernel(const GemmArgs a, in
     return g < n_groups ? g : n_groups;
   };
 
-  // ---- loader addressing: one instruction fills 16 tile rows (lane -> row lane/4, LDS chunk lane%4);
-  //      wave w moves rows [32w, 32w + 32) of both operand tiles.  Addresses are a wave-uniform
-  //      64-bit base (scalar registers) plus a per-lane 32-bit byte offset that never changes.
-  const int ld_row = wave * 32 + (lane >> 2);
-  const int ld_chunk = (lane & 3) ^ ((lane >> 4) & 3);  // logical chunk that lands in LDS chunk lane%4
-  const uint32_t offA = (uint32_t)(ld_row * a.lda + ld_chunk * 8) * 2u;
-  const uint32_t offW = (uint32_t)(ld_row * a.ldw + ld_chunk * 8) * 2u;
-  const size_t a_step = (size_t)32 * a.lda, w_step = (size_t)32 * a.ldw;  // bytes per 16 rows
+  // ---- loader addressing: one instruction fills 8 tile rows of 128 bytes (lane -> row lane/8, LDS
+  //      chunk lane%8); wave w moves rows [32w, 32w + 32) of both operand tiles.  An address is a
+  //      wave-uniform 64-bit base (scalar registers) plus a per-lane 32-bit byte offset that never
+  //      changes.  The logical chunk that lands in LDS chunk c of row r is c ^ ((r >> 1) & 7); for
+  //      row 32w + 8i + lane/8 that is (4 * (i & 1) + lane/16) & 7: two offset variants per operand.
+  const int ld_row = wave * 32 + (lane >> 3);
+  const int ld_chunk = (lane & 7) ^ (lane >> 4);
+  const uint32_t offA0 = (uint32_t)(ld_row * a.lda + ld_chunk * 8) * 2u;
+  const uint32_t offA1 = (uint32_t)(ld_row * a.lda + (ld_chunk ^ 4) * 8) * 2u;
+  const uint32_t offW0 = (uint32_t)(ld_row * a.ldw + ld_chunk * 8) * 2u;
+  const uint32_t offW1 = (uint32_t)(ld_row * a.ldw + (ld_chunk ^ 4) * 8) * 2u;
+  const size_t a_step = (size_t)16 * a.lda, w_step = (size_t)16 * a.ldw;  // bytes per 8 rows
   const unsigned char *baseA = nullptr, *baseW = nullptr;  // load cursor: uniform tile bases at k = 0
   int g_l = next_group(xcd), kt_l = 0;
   auto set_load_tile = [&]() {
@@ -428,21 +442,24 @@ __global__ __launch_bounds__(512) void gemm_bf16_dma_kernel(const GemmArgs a, in
     }
   };
   set_load_tile();
-  // one direct-to-LDS instruction of ring slot `st` at the load cursor: i in [0,2) -> A rows, [2,4) -> W rows
-  // The instruction is written as inline assembly so that the compiler's wait-count insertion, which
-  // cannot know that the ring slot written here is never one being read, does not fence every
-  // surrounding LDS read; completion is tracked by hand (sync_stage).  M0 holds the LDS base.
-  auto dma16 = [&](const unsigned char* gptr, unsigned char* lptr) {
+  // One direct-to-LDS instruction.  It is written as inline assembly so that the compiler's
+  // wait-count insertion, which cannot know that the stage written here is never one being read,
+  // does not fence every surrounding LDS read; completion is tracked by hand (sync_stage).  M0 holds
+  // the LDS destination of lane 0.
+  auto dma16 = [&](const unsigned char* gbase, uint32_t goff, unsigned char* lptr) {
     // low 32 bits of a generic LDS pointer = LDS offset; wave-uniform by construction
     const uint32_t lds_addr = __builtin_amdgcn_readfirstlane((uint32_t)(uintptr_t)lptr);
-    asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, off" ::"s"(lds_addr), "v"(gptr) : "memory", "m0");
+    asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, %2" ::"s"(lds_addr), "v"(goff), "s"(gbase)
+                 : "memory", "m0");
   };
+  // instruction i of stage slot `st` at the load cursor: i in [0,4) -> A rows 8i.., [4,8) -> W rows 8(i-4)..
   auto issue_load = [&](int st, int i) {
     unsigned char* base = smem + st * D_STAGE_BYTES;
-    if (i < 2)
-      dma16(baseA + i * a_step + kt_l * (D_BK * 2) + offA, base + (wave * 32 + i * 16) * 64);
+    if (i < 4)
+      dma16(baseA + i * a_step + kt_l * D_ROW, (i & 1) ? offA1 : offA0, base + (wave * 32 + i * 8) * D_ROW);
     else
-      dma16(baseW + (i - 2) * w_step + kt_l * (D_BK * 2) + offW, base + D_BM * 64 + (wave * 32 + (i - 2) * 16) * 64);
+      dma16(baseW + (i - 4) * w_step + kt_l * D_ROW, (i & 1) ? offW1 : offW0,
+            base + D_BM * D_ROW + (wave * 32 + (i - 4) * 8) * D_ROW);
   };
   const int KT = a.K / D_BK;
   auto advance_load_cursor = [&]() {
@@ -453,21 +470,20 @@ __global__ __launch_bounds__(512) void gemm_bf16_dma_kernel(const GemmArgs a, in
     }
   };
 
-  // ---- fragment addressing: row*64 + ((2ks + lk) ^ ((row >> 2) & 3)) * 16, row = 32-aligned base + lrow
-  const int sw = (lrow >> 2) & 3;
-  const uint32_t fa_off0 = (uint32_t)((wm * TM + lrow) * 64 + ((lk ^ sw) << 4));
-  const uint32_t fa_off1 = (uint32_t)((wm * TM + lrow) * 64 + (((2 + lk) ^ sw) << 4));
-  const uint32_t fb_off0 = (uint32_t)(D_BM * 64 + (wn * TN + lrow) * 64 + ((lk ^ sw) << 4));
-  const uint32_t fb_off1 = (uint32_t)(D_BM * 64 + (wn * TN + lrow) * 64 + (((2 + lk) ^ sw) << 4));
+  // ---- fragment addressing: row*128 + ((2ks + lk) ^ ((row >> 1) & 7)) * 16, row = 32-aligned base + lrow;
+  //      with pos0 = lk ^ sw the chunk of sub-step ks is pos0 ^ 2ks, i.e. the byte offset XOR (ks << 5)
+  const int sw = (lrow >> 1) & 7;
+  const uint32_t fa_off = (uint32_t)((wm * TM + lrow) * D_ROW + ((lk ^ sw) << 4));
+  const uint32_t fb_off = (uint32_t)(D_BM * D_ROW + (wn * TN + lrow) * D_ROW + ((lk ^ sw) << 4));
 
   f32x16 acc[FM][FN];
-  bf16x8 fa0[FM], fb0[FN], fa1[FM], fb1[FN];  // fragments of the two 16-wide halves of a k-step
+  bf16x8 fa0[FM], fb0[FN], fa1[FM], fb1[FN];  // fragments of even / odd sub-steps
 
   auto rd_a = [&](int st, int ks, int i) {
-    return *(const bf16x8*)(smem + st * D_STAGE_BYTES + (ks ? fa_off1 : fa_off0) + i * 32 * 64);
+    return *(const bf16x8*)(smem + st * D_STAGE_BYTES + (fa_off ^ (uint32_t)(ks << 5)) + i * 32 * D_ROW);
   };
   auto rd_b = [&](int st, int ks, int j) {
-    return *(const bf16x8*)(smem + st * D_STAGE_BYTES + (ks ? fb_off1 : fb_off0) + j * 32 * 64);
+    return *(const bf16x8*)(smem + st * D_STAGE_BYTES + (fb_off ^ (uint32_t)(ks << 5)) + j * 32 * D_ROW);
   };
   auto mm = [&](int i, const bf16x8& x, const bf16x8 (&w)[FN]) {
 #pragma unroll
@@ -479,72 +495,72 @@ __global__ __launch_bounds__(512) void gemm_bf16_dma_kernel(const GemmArgs a, in
   for (int g = next_group(xcd); g < n_groups; g = next_group(g + 8)) ++n_my_tiles;
   const int total_stages = n_my_tiles * KT;
   int issued = 0, consumed = 0;  // k-stages issued to the ring / multiplied so far
-  int landed = 0;  // stages [0, landed) are known to have landed (the ring was drained after they were issued)
-  int st_c = 0;    // ring slot of the stage being multiplied
+  int st_c = 0;                  // ring slot of the stage being multiplied
 
-  // Wait until stage `s` has landed for this wave (its own loads), then meet the other waves.
-  // Stages issued after `s` may be in flight.  The vector-memory counter also counts the epilogue's
-  // stores; "at most young*4 operations outstanding" bounds the outstanding loads from above and
-  // loads complete in issue order, so the wait is sufficient whatever the stores do.  All LDS
-  // reads of this wave are complete before the barrier (lgkmcnt(0)), so the slot read last may be
-  // overwritten by loads issued after the barrier.
-  auto sync_stage = [&](int s) {
-    const int young = issued - s - 1;
-    if (s < landed || young >= 4) __builtin_amdgcn_s_waitcnt(0xC07F);  // lgkmcnt(0) only
-    else if (young == 3) __builtin_amdgcn_s_waitcnt(0x007C);          // vmcnt(12) lgkmcnt(0)
-    else if (young == 2) __builtin_amdgcn_s_waitcnt(0x0078);          // vmcnt(8)
-    else if (young == 1) __builtin_amdgcn_s_waitcnt(0x0074);          // vmcnt(4)
-    else __builtin_amdgcn_s_waitcnt(0x0070);                          // vmcnt(0)
+  // Every load this wave has issued has landed and every LDS read it has issued is complete; then
+  // meet the other waves.  (The vector-memory counter also counts the epilogue's stores.)
+  auto sync_stage = [&]() {
+    __builtin_amdgcn_s_waitcnt(0x0070);  // vmcnt(0) lgkmcnt(0)
     __builtin_amdgcn_s_barrier();
   };
 
-  // One k-step, software-pipelined across the step boundary.
-  //   phase A: MFMAs of the first half (fragments already in registers) while the second half's
-  //            fragments are read;
-  //   middle:  the next stage must have landed for every wave (barrier); the barrier wait and the
-  //            LDS latency of the reads that follow hide behind the MFMAs already queued;
-  //   phase B: MFMAs of the second half while the NEXT step's first-half fragments are read and
-  //            the four loads of the stage four steps ahead go into the slot this step just freed.
-  // sched_barrier(0) fences keep each group's instructions together in this order.
-  auto k_step = [&](auto load_tag, auto next_tag) {
+  // One sub-step that multiplies fragment set (x, w) while reading sub-step `ks` of stage `st`
+  // into (nx, nw); with `late` set, load instructions late0 .. late0 + 3 of the stage being
+  // prefetched follow the four MFMA pairs.  sched_barrier(0) fences keep each group's instructions
+  // together in this order.
+  auto sub_step = [&](int st, int ks, const bf16x8 (&x)[FM], const bf16x8 (&w)[FN], bf16x8 (&nx)[FM],
+                      bf16x8 (&nw)[FN], bool late, int late0) {
+    nw[0] = rd_b(st, ks, 0); nw[1] = rd_b(st, ks, 1);
+    nx[0] = rd_a(st, ks, 0);
+    __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+    for (int i = 0; i < FM; ++i) {
+      mm(i, x[i], w);
+      if (i + 1 < FM) nx[i + 1] = rd_a(st, ks, i + 1);
+      if (late) issue_load(st ^ 1, late0 + i);
+      __builtin_amdgcn_sched_barrier(0);
+    }
+  };
+
+  // One 64-wide k-stage.  On entry fa0 / fb0 hold the fragments of its sub-step 0.
+  //   sub-steps 0..2: MFMAs of sub-step j while the fragments of sub-step j + 1 are read;
+  //   sync:           the other stage has landed for every wave and this stage's LDS is dead;
+  //   sub-step 3:     its MFMAs while sub-step 0 of the other stage is read and the first four loads
+  //                   of the stage after that go into the slot this stage just freed, one per MFMA
+  //                   pair; the other four follow in sub-step 0 of the next stage (eight in a row
+  //                   would queue up in the memory pipeline and hold back the MFMAs behind them).
+  bool pend = false;  // the second half of a stage's loads is still to be issued
+  auto k_stage = [&](auto load_tag, auto next_tag) {
     constexpr bool LOAD = decltype(load_tag)::value, NEXT = decltype(next_tag)::value;
-    const int sn = (st_c + 1) & (D_ST - 1);
-    fb1[0] = rd_b(st_c, 1, 0); fb1[1] = rd_b(st_c, 1, 1);
-    fa1[0] = rd_a(st_c, 1, 0);
+    const int sn = st_c ^ 1;
+    sub_step(st_c, 1, fa0, fb0, fa1, fb1, pend, 4);
+    if (pend) { advance_load_cursor(); pend = false; }
+    sub_step(st_c, 2, fa1, fb1, fa0, fb0, false, 0);
+    // the last fragments of this stage are read up front so that they are complete at the barrier
+    fb1[0] = rd_b(st_c, 3, 0); fb1[1] = rd_b(st_c, 3, 1);
+#pragma unroll
+    for (int i = 0; i < FM; ++i) fa1[i] = rd_a(st_c, 3, i);
     __builtin_amdgcn_sched_barrier(0);
-    mm(0, fa0[0], fb0); fa1[1] = rd_a(st_c, 1, 1);
+#pragma unroll
+    for (int i = 0; i < FM; ++i) mm(i, fa0[i], fb0);
     __builtin_amdgcn_sched_barrier(0);
-    mm(1, fa0[1], fb0); fa1[2] = rd_a(st_c, 1, 2);
-    __builtin_amdgcn_sched_barrier(0);
-    mm(2, fa0[2], fb0); fa1[3] = rd_a(st_c, 1, 3);
-    __builtin_amdgcn_sched_barrier(0);
-    mm(3, fa0[3], fb0);
-    __builtin_amdgcn_sched_barrier(0);
-    if (NEXT) sync_stage(consumed + 1);
+    if (NEXT) sync_stage();
     __builtin_amdgcn_sched_barrier(0);
     if (NEXT) { fb0[0] = rd_b(sn, 0, 0); fb0[1] = rd_b(sn, 0, 1); fa0[0] = rd_a(sn, 0, 0); }
     __builtin_amdgcn_sched_barrier(0);
-    mm(0, fa1[0], fb1);
-    if (NEXT) fa0[1] = rd_a(sn, 0, 1);
-    if (LOAD) issue_load(st_c, 0);
-    __builtin_amdgcn_sched_barrier(0);
-    mm(1, fa1[1], fb1);
-    if (NEXT) fa0[2] = rd_a(sn, 0, 2);
-    if (LOAD) issue_load(st_c, 1);
-    __builtin_amdgcn_sched_barrier(0);
-    mm(2, fa1[2], fb1);
-    if (NEXT) fa0[3] = rd_a(sn, 0, 3);
-    if (LOAD) issue_load(st_c, 2);
-    __builtin_amdgcn_sched_barrier(0);
-    mm(3, fa1[3], fb1);
-    if (LOAD) issue_load(st_c, 3);
-    __builtin_amdgcn_sched_barrier(0);
-    if (LOAD) { advance_load_cursor(); ++issued; }
+#pragma unroll
+    for (int i = 0; i < FM; ++i) {
+      mm(i, fa1[i], fb1);
+      if (NEXT && i < FM - 1) fa0[i + 1] = rd_a(sn, 0, i + 1);
+      if (LOAD) issue_load(st_c, i);
+      __builtin_amdgcn_sched_barrier(0);
+    }
+    if (LOAD) { pend = true; ++issued; }
     ++consumed;
     st_c = sn;
   };
 
-  // ---- prologue: fill the ring, wait for the first stage, read its first-half fragments
+  // ---- prologue: fill both stages, wait for them, read the first fragments
   for (int i = 0; i < D_ST && issued < total_stages; ++i) {
 #pragma unroll
     for (int j = 0; j < D_LOADS; ++j) issue_load(i, j);
@@ -552,40 +568,35 @@ __global__ __launch_bounds__(512) void gemm_bf16_dma_kernel(const GemmArgs a, in
     ++issued;
   }
   if (total_stages > 0) {
-    sync_stage(0);
+    sync_stage();
     fb0[0] = rd_b(0, 0, 0); fb0[1] = rd_b(0, 0, 1);
 #pragma unroll
     for (int i = 0; i < FM; ++i) fa0[i] = rd_a(0, 0, i);
   }
 
   for (int g_c = next_group(xcd); g_c < n_groups; g_c = next_group(g_c + 8)) {
+    int tm, tn;
+    tile_of(g_c, tm, tn);
+    const int row0 = tm * D_BM + wm * TM, ncol0 = tn * D_BN + wn * TN;
 #pragma unroll
     for (int i = 0; i < FM; ++i)
 #pragma unroll
       for (int j = 0; j < FN; ++j)
 #pragma unroll
         for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
-    int tm, tn;
-    tile_of(g_c, tm, tn);
-    const int row0 = tm * D_BM + wm * TM, ncol0 = tn * D_BN + wn * TN;
-    // steps that still prefetch a stage; then (only at the end of the list) steps that only read
-    // ahead; then the very last step of the list, which has nothing after it
+    // stages that still prefetch one; then (only at the end of the list) a stage that only reads
+    // ahead; then the very last stage of the list, which has nothing after it
     const int n_ld = min(KT, total_stages - issued);
     const int n_nx = min(KT, total_stages - 1 - consumed);
-    for (int kt = 0; kt < n_ld; ++kt) k_step(std::true_type{}, std::true_type{});
-    for (int kt = n_ld; kt < n_nx; ++kt) k_step(std::false_type{}, std::true_type{});
-    for (int kt = max(n_ld, n_nx); kt < KT; ++kt) k_step(std::false_type{}, std::false_type{});
+    for (int kt = 0; kt < n_ld; ++kt) k_stage(std::true_type{}, std::true_type{});
+    for (int kt = n_ld; kt < n_nx; ++kt) k_stage(std::false_type{}, std::true_type{});
+    for (int kt = max(n_ld, n_nx); kt < KT; ++kt) k_stage(std::false_type{}, std::false_type{});
     asm volatile("" ::: "memory");  // keep the epilogue's loads below the k-loop
-    // The epilogue's first loads (bias, residual rows) queue behind the operand ring, so waiting for
-    // them drains the ring: every stage issued so far has landed and the next steps need no counter
-    // wait for them.  The epilogue's stores are never waited for explicitly.
     f32x4 bias[FN][4];
 #pragma unroll
     for (int j = 0; j < FN; ++j)
 #pragma unroll
       for (int jj = 0; jj < 4; ++jj) bias[j][jj] = *(const f32x4*)(a.bias + ncol0 + j * 32 + jj * 8 + lk * 4);
-    __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0)
-    landed = issued;
     wave_epilogue_p<EPI>(a, acc, bias, staging + wave * 16 * D_STAGING_ROW, row0, ncol0, lane);
   }
 }

@@ -366,7 +366,7 @@ void plan_workspace(const Dims& d, int64_t n_tiles, Workspace* w) {
   w->n_tok = n_tiles * d.T;
   w->Mpad = round_up(std::max<int64_t>(w->n_tok, 1), pad);
   w->patch_rows_pad = round_up(std::max<int64_t>(n_tiles * d.P, 1), pad);
-  const int bq = attention_q_block(d.bf16);
+  const int bq = attention_q_block(d.bf16, d.dhp);
   w->max_work = n_tiles * ((d.T + bq - 1) / bq);
   size_t off = 0;
   auto carve = [&](size_t bytes) { size_t o = off; off += (bytes + 255) / 256 * 256; return o; };
@@ -456,7 +456,7 @@ vit_status_t vit_encode_packed(vit_encoder_t* e, const float* pixels, const int3
   const int n_tok = (int)w.n_tok;
 
   // ---- segment planning: blocks of query rows per tile (local layers) and per image (global layers)
-  const int bq = attention_q_block(d.bf16);
+  const int bq = attention_q_block(d.bf16, d.dhp);
   const bool has_global = d.L > d.L_loc;
   int n_local = 0, n_global = 0;
   {
