@@ -20,6 +20,8 @@
 // waves per SIMD (from different workgroups) let one wave's VALU phase overlap the other's MFMAs.
 // K/V tiles of 64 keys are double-buffered in LDS: the next tile's global loads are issued before
 // the current tile is processed and written to the other buffer afterwards (one barrier per tile).
+#include <type_traits>
+
 #include "common.h"
 
 namespace vitenc {
@@ -50,7 +52,7 @@ struct AttnShape {
 };
 
 template <int DHP, int QB, int NW>
-__global__ __launch_bounds__(64 * NW, 2) void attention_bf16_kernel(const AttnArgs a, float scale_log2) {
+__global__ __launch_bounds__(64 * NW, QB == 1 ? (DHP == 64 ? 4 : DHP <= 96 ? 3 : 2) : 2) void attention_bf16_kernel(const AttnArgs a, float scale_log2) {
   using Sh = AttnShape<DHP, QB, NW>;
   constexpr int ANT = Sh::ANT;
   extern __shared__ __attribute__((aligned(16))) unsigned char lds[];  // 2 stages of (K tile, V^T tile)
@@ -161,7 +163,10 @@ __global__ __launch_bounds__(64 * NW, 2) void attention_bf16_kernel(const AttnAr
   store_tile(lds, lds + Sh::K_BYTES);
   __syncthreads();
 
-  for (int t = 0; t < n_tiles; ++t) {
+  // One K/V tile.  MASK is set only for a segment's last, partial tile: full tiles carry no
+  // per-logit compare/select at all.
+  auto process_tile = [&](int t, auto mask_tag) {
+    constexpr bool MASK = decltype(mask_tag)::value;
     const unsigned char* sK = lds + (t & 1) * Sh::STAGE;
     const unsigned char* sVt = sK + Sh::K_BYTES;
     if (t + 1 < n_tiles) load_tile((t + 1) * AKV);
@@ -184,7 +189,7 @@ __global__ __launch_bounds__(64 * NW, 2) void attention_bf16_kernel(const AttnAr
           st[qb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[qb][ks], st[qb], 0, 0, 0);
       }
       // ---- mask keys past the segment end (only a segment's last tile has any)
-      if (remaining < AKV) {
+      if (MASK) {
 #pragma unroll
         for (int qb = 0; qb < QB; ++qb)
 #pragma unroll
@@ -251,7 +256,10 @@ __global__ __launch_bounds__(64 * NW, 2) void attention_bf16_kernel(const AttnAr
       store_tile(nK, nK + Sh::K_BYTES);
     }
     __syncthreads();
-  }
+  };
+  const int n_full = w.seg_len / AKV;  // tiles with all 64 keys valid
+  for (int t = 0; t < n_full; ++t) process_tile(t, std::false_type{});
+  if (n_full < n_tiles) process_tile(n_full, std::true_type{});
 
   // ---- normalise and store: lane owns a query; registers 4j..4j+3 of block b are
   //      d = 32b + 8j + 4g .. +3, four consecutive columns -> one 8-byte store
@@ -279,7 +287,7 @@ __global__ __launch_bounds__(64 * NW, 2) void attention_bf16_kernel(const AttnAr
 
 }  // namespace
 
-int attention_q_block(int dtype_bf16, int dh_pad) { return !dtype_bf16 ? 64 : dh_pad == 64 ? 128 : 256; }
+int attention_q_block(int dtype_bf16, int dh_pad) { return !dtype_bf16 ? 64 : 128; }  // 32 * QB * NW
 
 hipError_t launch_attention_bf16(const AttnArgs& a, hipStream_t s) {
   if (a.n_work <= 0) return hipSuccess;
@@ -299,10 +307,10 @@ hipError_t launch_attention_bf16(const AttnArgs& a, hipStream_t s) {
     hipLaunchKernelGGL(kfn, grid, dim3(AttnShape<DHP, QB, NW>::ANT), smem, s, a, scale_log2);          \
   } while (0)
   switch (a.dh_pad) {
-    case 64: VIT_ATTN(64, 2, 2); break;
-    case 80: VIT_ATTN(80, 2, 4); break;
-    case 96: VIT_ATTN(96, 2, 4); break;
-    case 128: VIT_ATTN(128, 1, 8); break;
+    case 64: VIT_ATTN(64, 1, 4); break;
+    case 80: VIT_ATTN(80, 1, 4); break;
+    case 96: VIT_ATTN(96, 1, 4); break;
+    case 128: VIT_ATTN(128, 1, 4); break;
     default: return hipErrorInvalidValue;
   }
 #undef VIT_ATTN
