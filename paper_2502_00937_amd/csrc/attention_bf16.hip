@@ -159,6 +159,8 @@ __global__ __launch_bounds__(64 * NW, QB == 1 ? (DHP == 64 ? 4 : DHP <= 96 ? 3 :
   };
 
   const int n_tiles = (w.seg_len + AKV - 1) / AKV;
+  // a wave whose 32 * QB query rows all lie past the segment end (last block of a segment) skips the arithmetic
+  const bool wave_active = w.q0 + wave * QB * 32 < seg_end;
   load_tile(0);
   store_tile(lds, lds + Sh::K_BYTES);
   __syncthreads();
@@ -175,6 +177,8 @@ __global__ __launch_bounds__(64 * NW, QB == 1 ? (DHP == 64 ? 4 : DHP <= 96 ? 3 :
     // the tile is processed in two 32-key halves to keep S^T and P^T small in registers
 #pragma unroll
     for (int kb = 0; kb < 2; ++kb) {
+      if (!wave_active) break;  // (the wave still stages K / V and meets the barriers)
+      if (MASK && kb * 32 >= remaining) break;  // the second half of the last tile may hold no key at all
       // ---- S^T = K . Q^T: each K fragment feeds all query blocks of the wave
       f32x16 st[QB];
 #pragma unroll
