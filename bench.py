@@ -26,7 +26,7 @@ HBM_PEAK_GBS = 8000.0
 # HBM-side bytes of all matrix-product launches of ONE cfg3 step, from the two rocprofv3 --pmc runs
 # (FETCH_SIZE x 2.0 + WRITE_SIZE x 1.0, factors from the copy calibration) summarised in
 # profiles/kernels_cfg3_ragged_hbm_traffic.md.  A profile figure, not measured by this script.
-GEMM_TRAFFIC_BYTES_PER_STEP = {"cfg3": 257.3e9}
+GEMM_TRAFFIC_BYTES_PER_STEP = {"cfg3": 258.3e9}
 
 
 def flops(cfg, tile_offsets):
@@ -72,7 +72,7 @@ def main():
     ap.add_argument("--steps", type=int, default=10)
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--workload", default="cfg3", choices=["cfg1", "cfg2", "cfg3", "cfg4", "cfg5"])
-    ap.add_argument("--cpu-sample", type=int, default=4, help="images the CPU oracle encodes (0 = skip)")
+    ap.add_argument("--cpu-sample", type=int, default=12, help="images the CPU oracle encodes (0 = skip)")
     ap.add_argument("--no-kernel-events", action="store_true", help="time the steps without per-kernel events")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="run five plain 1 GiB device copies and exit (scale reference for rocprofv3 FETCH_SIZE / WRITE_SIZE)")
