@@ -66,6 +66,40 @@ def cpu_baseline(cfg, weights, px, tile_offsets, n_sample):
     }
 
 
+def sweep(args, torch, gen, V):
+    """Throughput against images per launch (Sec. 3.2: encode time grows linearly with the batch once the
+    device is full) and the config-3 batch under three request packings."""
+    cfg, ipr3, to3 = gen.make_workload("cfg3")
+    weights = gen.make_weights(cfg, seed=0)
+    enc = V.VitEncoder(cfg, weights, device=0)
+    px = torch.from_numpy(gen.make_pixels(cfg, 260, seed=1)).cuda()
+    T = gen.tokens_per_tile(cfg)
+
+    def timed(n, ipr, label):
+        to = np.arange(n + 1, dtype=np.int32)
+        n_tok, out_dim, _, _ = enc.query(n, n)
+        out = torch.empty((n_tok, out_dim), dtype=torch.bfloat16, device="cuda")
+        for _ in range(2):
+            enc.encode(px[:n], ipr, to, out=out)
+        torch.cuda.synchronize()
+        steps = max(3, min(50, int(2000 / max(n, 1))))
+        t0 = time.perf_counter()
+        for _ in range(steps):
+            enc.encode(px[:n], ipr, to, out=out)
+        torch.cuda.synchronize()
+        ms = (time.perf_counter() - t0) / steps * 1e3
+        total_f, _, _ = flops(cfg, to)
+        print(json.dumps({"sweep": label, "images": n, "requests": int(len(ipr)), "tokens": n * T, "ms_per_launch": ms,
+                          "images_per_s": n / (ms * 1e-3), "pct_bf16_peak": 100.0 * total_f / (ms * 1e-3) / 1e12 / PEAK_BF16_TFLOPS}))
+
+    for n in (1, 8, 64, 260):
+        timed(n, np.ones(n, dtype=np.int32), "images per launch")
+    timed(260, ipr3, "cfg3 as 64 ragged requests")
+    timed(260, np.ones(260, dtype=np.int32), "cfg3 as 260 single-image requests")
+    timed(260, np.asarray([260], dtype=np.int32), "cfg3 as one request of 260 images")
+    enc.close()
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -74,6 +108,9 @@ def main():
     ap.add_argument("--workload", default="cfg3", choices=["cfg1", "cfg2", "cfg3", "cfg4", "cfg5"])
     ap.add_argument("--cpu-sample", type=int, default=12, help="images the CPU oracle encodes (0 = skip)")
     ap.add_argument("--no-kernel-events", action="store_true", help="time the steps without per-kernel events")
+    ap.add_argument("--sweep", action="store_true",
+                    help="instead of the benchmark line: encode 1, 8, 64 and 260 images of the config-3 model (one JSON "
+                         "line per size) and config 3 repacked as 260 single-image requests / one 260-image request")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="run five plain 1 GiB device copies and exit (scale reference for rocprofv3 FETCH_SIZE / WRITE_SIZE)")
     args = ap.parse_args()
@@ -97,6 +134,9 @@ def main():
         torch.cuda.synchronize()
         print(json.dumps({"copy_calibration": {"bytes_read": 1 << 30, "bytes_written": 1 << 30, "copies": 5}}))
         return
+    if args.sweep:
+        sweep(args, torch, gen, V)
+        return
     cfg, ipr, to = gen.make_workload(args.workload)
     n_images, n_tiles = int(ipr.sum()), int(to[-1])
     T = gen.tokens_per_tile(cfg)
@@ -113,13 +153,17 @@ def main():
     torch.cuda.synchronize()
     if not args.no_kernel_events:
         enc.profile_enable(True)
+    marks = [torch.cuda.Event(enable_timing=True) for _ in range(args.steps + 1)]  # on the launch stream
     torch.cuda.synchronize()
     t0 = time.perf_counter()
-    for _ in range(args.steps):
+    marks[0].record()
+    for i in range(args.steps):
         enc.encode(px_dev, ipr, to, out=out)
+        marks[i + 1].record()
     torch.cuda.synchronize()
     dt = time.perf_counter() - t0
     ms_per_step = dt / args.steps * 1e3
+    step_ms = sorted(marks[i].elapsed_time(marks[i + 1]) for i in range(args.steps))
 
     total_f, gemm_f, attn_f = flops(cfg, to)
     result = {
@@ -137,6 +181,7 @@ def main():
             "requests": int(len(ipr)), "images": n_images, "tiles": n_tiles, "tokens": int(n_tok),
             "weights": "seeded N(0, 0.02), bf16-rounded", "pixels": "seeded U[-1,1), resident in HBM",
         },
+        "ms_per_step_median": step_ms[len(step_ms) // 2], "ms_per_step_min": step_ms[0],
         "tokens_per_s": n_tok / (ms_per_step * 1e-3),
         "tiles_per_s": n_tiles / (ms_per_step * 1e-3),
         "tflops": total_f / (ms_per_step * 1e-3) / 1e12,
@@ -149,8 +194,9 @@ def main():
         gemm_ms, gemm_n = prof["gemm"][0] / args.steps, prof["gemm"][1] // args.steps
         achieved = gemm_f / (gemm_ms * 1e-3) / 1e12
         result["roofline"] = {
-            "bound": "mfma", "kernel": "gemm_bf16_kernel (all matrix products of one step)",
+            "bound": "mfma", "kernel": "gemm_bf16_dma_kernel (all matrix products of one step)",
             "achieved": achieved, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": achieved / PEAK_BF16_TFLOPS,
+            "measured_mfma_ceiling": V.vit_mfma_ceiling(0, 0.1),  # register-only MFMA loop on this device, TFLOP/s
             "traffic": GEMM_TRAFFIC_BYTES_PER_STEP.get(args.workload), "traffic_unit": "bytes per step (all launches), rocprofv3 --pmc",
             "launches_per_step": int(gemm_n), "ms_per_step": gemm_ms,
             "avg_launch_ms": gemm_ms / max(gemm_n, 1), "flop_per_step": gemm_f,

@@ -144,6 +144,17 @@ enum {
 vit_status_t vit_profile_enable(vit_encoder_t* enc, int enable);
 vit_status_t vit_profile_read(vit_encoder_t* enc, double* ms, int64_t* launches);
 
+/*
+ * Measurement aid (no part of the encode path): runs a register-only bf16 MFMA loop
+ * (v_mfma_f32_32x32x16_bf16, two waves per SIMD, no memory traffic) on `device` for about
+ * `seconds` (0 < seconds <= 2) on the null stream and writes the sustained rate in TFLOP/s
+ * to *tflops (host pointer).  This is the practical ceiling of the matrix cores on the
+ * device at hand, printed by the benchmark beside the nominal peak that every reported
+ * fraction uses.  Allocates and frees 1 KiB of device memory; synchronises the device's
+ * null stream.  Errors: VIT_EINVAL (NULL / range), VIT_EDEVICE.
+ */
+vit_status_t vit_mfma_ceiling(int device, double seconds, double* tflops);
+
 #pragma GCC visibility pop
 #ifdef __cplusplus
 }

@@ -12,5 +12,6 @@ from .binding import (  # noqa: F401
     vit_encoder_create,
     vit_encoder_destroy,
     vit_encoder_query,
+    vit_mfma_ceiling,
     vit_weight_count,
 )

@@ -58,6 +58,8 @@ def load_library():
     lib.vit_encoder_destroy.argtypes = [C.c_void_p]
     lib.vit_profile_enable.restype = C.c_int
     lib.vit_profile_enable.argtypes = [C.c_void_p, C.c_int]
+    lib.vit_mfma_ceiling.restype = C.c_int
+    lib.vit_mfma_ceiling.argtypes = [C.c_int, C.c_double, C.POINTER(C.c_double)]
     lib.vit_profile_read.restype = C.c_int
     lib.vit_profile_read.argtypes = [C.c_void_p, C.POINTER(C.c_double), C.POINTER(C.c_int64)]
     _LIB = lib
@@ -114,6 +116,13 @@ def vit_encode_packed(handle: int, pixels_ptr: int, images_per_request, tile_off
                                             to.ctypes.data, out_ptr, out_capacity_bytes, rto.ctypes.data,
                                             workspace_ptr, workspace_bytes, stream))
     return rto
+
+
+def vit_mfma_ceiling(device: int = 0, seconds: float = 0.1) -> float:
+    """Sustained TFLOP/s of a register-only bf16 MFMA loop on `device` (measurement aid)."""
+    out = C.c_double(0.0)
+    _check(load_library().vit_mfma_ceiling(int(device), float(seconds), C.byref(out)))
+    return out.value
 
 
 def vit_encoder_destroy(handle: int) -> None:

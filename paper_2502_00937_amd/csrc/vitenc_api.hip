@@ -214,6 +214,28 @@ struct ProfScope {
   }
 };
 
+// Register-only MFMA loop: eight independent 32x32 accumulators per wave, no memory traffic.  What it
+// sustains is the matrix cores' practical ceiling on this device (the clock the chip holds under
+// full MFMA load times the issue rate), the yardstick beside the nominal peak.
+__global__ __launch_bounds__(256) void mfma_ceiling_kernel(float* out, int iters) {
+  bf16x8 a, b;
+  for (int i = 0; i < 8; ++i) {
+    a[i] = (__bf16)(0.001f * (float)(threadIdx.x + i));
+    b[i] = (__bf16)(0.002f * (float)(threadIdx.x % 7 + i));
+  }
+  f32x16 acc[8];
+  for (int j = 0; j < 8; ++j)
+    for (int v = 0; v < 16; ++v) acc[j][v] = 0.f;
+  for (int it = 0; it < iters; ++it) {
+#pragma unroll
+    for (int j = 0; j < 8; ++j) acc[j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, acc[j], 0, 0, 0);
+  }
+  float sum = 0.f;
+  for (int j = 0; j < 8; ++j)
+    for (int v = 0; v < 16; ++v) sum += acc[j][v];
+  if (sum == 123.456f) out[threadIdx.x] = sum;  // keeps the loop alive; never true in practice
+}
+
 }  // namespace
 
 extern "C" {
@@ -581,6 +603,42 @@ vit_status_t vit_profile_read(vit_encoder_t* e, double* ms, int64_t* launches) {
   }
   e->prof.clear();
   for (int i = 0; i < VIT_PROF_COUNT; ++i) { ms[i] = e->prof_ms[i]; launches[i] = e->prof_n[i]; }
+  return VIT_OK;
+}
+
+vit_status_t vit_mfma_ceiling(int device, double seconds, double* tflops) {
+  if (!tflops || !(seconds > 0.0) || seconds > 2.0) return fail(VIT_EINVAL, "vit_mfma_ceiling: bad argument");
+  HIP_TRY(hipSetDevice(device));
+  int n_cu = 0;
+  HIP_TRY(hipDeviceGetAttribute(&n_cu, hipDeviceAttributeMultiprocessorCount, device));
+  float* out = nullptr;
+  HIP_TRY(hipMalloc(&out, 256 * sizeof(float)));
+  hipEvent_t e0 = nullptr, e1 = nullptr;
+  hipError_t err = hipEventCreate(&e0);
+  if (err == hipSuccess) err = hipEventCreate(&e1);
+  const int grid = 2 * n_cu;  // 4 waves per workgroup, 2 workgroups per unit: two waves per SIMD
+  const double flop_per_iter = (double)grid * 4 * 8 * 2.0 * 32 * 32 * 16;
+  double best = 0.0;
+  int iters = 20000;  // about 5 ms; the second launch is sized from the first to last `seconds`
+  for (int rep = 0; rep < 2 && err == hipSuccess; ++rep) {
+    err = hipEventRecord(e0, 0);
+    if (err != hipSuccess) break;
+    hipLaunchKernelGGL(mfma_ceiling_kernel, dim3(grid), dim3(256), 0, 0, out, iters);
+    err = hipGetLastError();
+    if (err == hipSuccess) err = hipEventRecord(e1, 0);
+    if (err == hipSuccess) err = hipEventSynchronize(e1);
+    float ms = 0.f;
+    if (err == hipSuccess) err = hipEventElapsedTime(&ms, e0, e1);
+    if (err != hipSuccess || ms <= 0.f) break;
+    best = flop_per_iter * iters / (ms * 1e-3) / 1e12;
+    const double want = (double)iters * (seconds * 1e3 / ms);
+    iters = (int)(want < 1000.0 ? 1000.0 : want > 4.0e6 ? 4.0e6 : want);
+  }
+  if (e0) (void)hipEventDestroy(e0);
+  if (e1) (void)hipEventDestroy(e1);
+  (void)hipFree(out);
+  if (err != hipSuccess) return fail(VIT_EDEVICE, "vit_mfma_ceiling: %s", hipGetErrorString(err));
+  *tflops = best;
   return VIT_OK;
 }
 

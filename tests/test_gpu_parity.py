@@ -161,3 +161,13 @@ def test_profile_counters():
     assert all(v[0] > 0 for v in prof.values())
     enc.profile_enable(False)
     enc.close()
+
+
+@pytest.mark.gpu
+def test_mfma_ceiling_probe_reports_a_plausible_rate():
+    import paper_2502_00937_amd as V
+
+    say("case mfma ceiling probe, 0.05 s")
+    t = V.vit_mfma_ceiling(0, 0.05)
+    say(f"    register-only MFMA loop: {t:.0f} TFLOP/s")
+    assert 500.0 < t < 2600.0  # below the 2.5 PFLOP/s nominal peak (+ clock tolerance), far above any VALU rate

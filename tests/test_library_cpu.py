@@ -23,9 +23,21 @@ def test_library_loads_and_exports_every_declared_symbol():
     lib = V.load_library()
     names = declared_symbols()
     assert {"vit_encoder_create", "vit_encode_packed", "vit_encoder_destroy", "vit_encoder_query",
-            "vit_weight_count", "vit_last_error", "vit_profile_enable", "vit_profile_read"} <= set(names)
+            "vit_weight_count", "vit_last_error", "vit_profile_enable", "vit_profile_read",
+            "vit_mfma_ceiling"} <= set(names)
     for n in names:
         assert hasattr(lib, n), n
+
+
+def test_mfma_ceiling_rejects_bad_arguments_before_touching_a_device():
+    import ctypes as C
+
+    lib = V.load_library()
+    out = C.c_double(-1.0)
+    assert lib.vit_mfma_ceiling(0, 0.1, None) == -1      # VIT_EINVAL: NULL result pointer
+    assert lib.vit_mfma_ceiling(0, 0.0, C.byref(out)) == -1
+    assert lib.vit_mfma_ceiling(0, 5.0, C.byref(out)) == -1
+    assert out.value == -1.0
 
 
 def test_struct_matches_header_field_order():
