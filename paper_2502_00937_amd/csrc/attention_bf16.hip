@@ -1,4 +1,4 @@
-// Variable-length flash attention on bf16 MFMA.  A work item is a block of 128 or 256 query rows of
+// Variable-length flash attention on bf16 MFMA.  A work item is a block of 128 query rows of
 // one segment (a tile, or all tiles of an image); keys never come from outside the segment, so
 // no padding or masking crosses images.
 //
@@ -12,12 +12,15 @@
 // place: registers 8s..8s+7 of an S^T block are exactly the 8 k-values lane group g feeds
 // to k-step s, provided V^T is read in the same key order (keys 16s + 8jj + 4g + i).
 //
-// The softmax arithmetic (exp2, max, sum, convert: plain VALU work) costs more cycles than the
-// two products, so the kernel is shaped around it: a wave owns 64 queries (two 32-query blocks)
-// so every K and V^T fragment read from LDS feeds two MFMAs; the logit scale is folded into the
-// exp2 argument (one fma per element); masking runs only on a segment's last key tile; the
-// output accumulator is rescaled only when some lane's running maximum actually moved; two
-// waves per SIMD (from different workgroups) let one wave's VALU phase overlap the other's MFMAs.
+// On gfx950 the VALU instructions of a SIMD hardly overlap its MFMAs, so the softmax arithmetic
+// (exp2, fma, max, sum, convert) and the two products share one issue budget, and the kernel is
+// shaped around instruction count and latency hiding: a wave owns 32 queries, which keeps it at
+// 124-168 VGPRs so that three or four waves (from different workgroups) share a SIMD and the
+// hardware interleaves their dependency chains; the logit scale is folded into the exp2 argument
+// (one fma per element); full key tiles carry no mask code at all (a segment's last tile is a
+// separate instantiation that also skips an empty key half, and waves with no valid query row skip
+// the arithmetic); the output accumulator is rescaled only when some lane's logits outgrow the
+// reference maximum by 2^8.
 // K/V tiles of 64 keys are double-buffered in LDS: the next tile's global loads are issued before
 // the current tile is processed and written to the other buffer afterwards (one barrier per tile).
 #include <type_traits>
@@ -32,8 +35,8 @@ constexpr int AKV = 64;  // keys per LDS tile
 constexpr float RESCALE_SLACK = 8.0f;  // log2 units the logits may exceed the reference maximum by
 
 // QB = 32-query blocks per wave, NW = waves per workgroup: a work item is 32 * QB * NW query rows.
-// Head dim 64 runs 2 x 2 (128 rows); the wider heads run 2 x 4 (256 rows), where the K/V staging
-// registers per thread halve and the 64-query wave still fits the register file.
+// All head dims run QB = 1, NW = 4 (128 rows); QB = 2 (each K / V^T fragment feeding two MFMAs, two
+// waves per SIMD) was measured 15 % slower.
 template <int DHP, int QB, int NW>
 struct AttnShape {
   static constexpr int ANT = 64 * NW;            // threads per workgroup

@@ -3,13 +3,15 @@
 // Both operands are K-contiguous, so a lane's 8 consecutive k values are one 16-byte
 // load and map directly onto the v_mfma_f32_32x32x16_bf16 operand registers.
 //
-// * Workgroup tile BM x BN x 64.  The 256 x 256 tile runs 8 waves (two per SIMD: one wave
-//   alone cannot keep a matrix core issuing back to back), each owning 128 x 64.
+// Two kernels share the fragment layout and the epilogues:
+// * gemm_bf16_kernel (below 256 tiles of 256 x 256): one 128 x 128 x 64 tile per workgroup, four
+//   waves of 64 x 64, operands staged global -> registers -> LDS with two LDS stages, one barrier
+//   per k-step, the loads of step k+1 in flight while step k is multiplied.
+// * gemm_bf16_dma_kernel (everything large): persistent, 256 x 256 tiles, eight waves of 128 x 64,
+//   operands global -> LDS directly; described where it is defined.
 // * LDS tiles are [row][64 bf16] with the 16-byte chunks XOR-swizzled by (row >> 1) & 7:
 //   LDS serves a 16-byte-per-lane read 16 lanes at a time over 64 banks, and this
 //   swizzle makes any 16 consecutive rows of one logical chunk hit 16 distinct bank groups.
-// * Two LDS stages, one barrier per k-step, global loads for step k+1 in flight while step
-//   k is multiplied.
 // * The product is formed transposed (W fragment as the MFMA row operand), so a lane ends
 //   up with four consecutive output columns of one token row per register quad.  The
 //   epilogue adds bias, applies GELU / residual, converts, stages the 32 x TN block of a
