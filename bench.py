@@ -91,13 +91,39 @@ def sweep(args, torch, gen, V):
         total_f, _, _ = flops(cfg, to)
         print(json.dumps({"sweep": label, "images": n, "requests": int(len(ipr)), "tokens": n * T, "ms_per_launch": ms,
                           "images_per_s": n / (ms * 1e-3), "pct_bf16_peak": 100.0 * total_f / (ms * 1e-3) / 1e12 / PEAK_BF16_TFLOPS}))
+        return ms
 
+    points = []
     for n in (1, 8, 64, 260):
-        timed(n, np.ones(n, dtype=np.int32), "images per launch")
+        points.append((n, timed(n, np.ones(n, dtype=np.int32), "images per launch")))
     timed(260, ipr3, "cfg3 as 64 ragged requests")
     timed(260, np.ones(260, dtype=np.int32), "cfg3 as 260 single-image requests")
     timed(260, np.asarray([260], dtype=np.int32), "cfg3 as one request of 260 images")
     enc.close()
+
+    # Stage profile -> maximum batch and capacity under a latency SLO (Sec. 4.2), then the two routing
+    # policies of Sec. 4.3 on a seeded heavy-tailed request stream, four Image Instances modelled with
+    # the latencies just measured.
+    from paper_2502_00937_amd import router as R
+    from paper_2502_00937_amd import stage_profile as SP
+
+    profile = [SP.ProfilePoint(n, n * T, ms) for n, ms in points]
+    for slo in (10.0, 25.0, 50.0, 100.0):
+        b = SP.max_batch_under_slo(profile, slo)
+        mc = SP.capacity_tokens_per_s(profile, slo, T)
+        print(json.dumps({"stage_profile": "max batch under SLO", "slo_ms": slo, "max_images_per_launch": b,
+                          "capacity_image_tokens_per_s": mc,
+                          "replicas_for_5M_tokens_per_s": SP.replicas(5e6, mc) if mc > 0 else None}))
+    lat = lambda images, tiles: SP.latency_at(profile, images)  # noqa: E731
+    b50 = max(1, SP.max_batch_under_slo(profile, 50.0))
+    for gap in (8.0, 4.0, 3.0):  # mean inter-arrival time in ms; about 4 images per request
+        arrivals = gen.make_arrivals(4000, gap, seed=0)
+        for policy in ("round_robin_request", "least_image_tokens"):
+            r = np.asarray(R.simulate(arrivals, 4, T, lat, b50, policy))
+            print(json.dumps({"routing": policy, "instances": 4, "mean_interarrival_ms": gap, "requests": len(arrivals),
+                              "images": int(sum(len(t) for _, t in arrivals)), "max_images_per_launch": b50,
+                              "encode_latency_ms": {"p50": float(np.percentile(r, 50)), "p90": float(np.percentile(r, 90)),
+                                                    "p99": float(np.percentile(r, 99)), "max": float(r.max())}}))
 
 
 def main():

@@ -8,6 +8,7 @@ from .configs import CONFIGS, get_config, tokens_per_tile, weight_count  # noqa:
 from .inputs import (  # noqa: F401
     CFG3_IMAGES_PER_REQUEST,
     CFG4_TILES_PER_IMAGE,
+    make_arrivals,
     make_pixels,
     make_weights,
     make_workload,

@@ -94,3 +94,19 @@ __all__ = [
     "CFG3_IMAGES_PER_REQUEST", "CFG4_TILES_PER_IMAGE", "round_to_bf16", "make_weights",
     "make_pixels", "make_workload", "tokens_per_tile",
 ]
+
+
+def make_arrivals(n_requests: int, mean_interarrival_ms: float, seed: int = 0, tiles_per_image: int = 1,
+                  max_images: int = 32):
+    """Seeded request stream for the routing experiments: Poisson arrivals, images per request drawn
+    from the same heavy-tailed recipe as the ragged batch (log-normal(0, 1.8), rounded, clipped to
+    [1, max_images]: median 1, a few requests with tens of images).  Returns a list of
+    (arrival time in ms, [tiles of every image])."""
+    rng = np.random.default_rng(seed)
+    t = 0.0
+    out = []
+    for _ in range(n_requests):
+        t += float(rng.exponential(mean_interarrival_ms))
+        n = int(np.clip(np.rint(rng.lognormal(0.0, 1.8)), 1, max_images))
+        out.append((t, [tiles_per_image] * n))
+    return out

@@ -171,3 +171,54 @@ def test_mfma_ceiling_probe_reports_a_plausible_rate():
     t = V.vit_mfma_ceiling(0, 0.05)
     say(f"    register-only MFMA loop: {t:.0f} TFLOP/s")
     assert 500.0 < t < 2600.0  # below the 2.5 PFLOP/s nominal peak (+ clock tolerance), far above any VALU rate
+
+
+@pytest.mark.gpu
+def test_routed_and_packed_launches_match_the_oracle_per_request():
+    """Requests of 3, 1, 4 and 2 images are routed image by image over two instances (here: two launch
+    queues on the one GPU), packed into launches of at most 3 images and encoded; every image's tokens
+    must match the oracle's encoding of that image alone, wherever the router and the packer put it."""
+    import torch
+
+    import paper_2502_00937_amd as V
+    from oracle import vit_oracle as O
+    from paper_2502_00937_amd.router import ImageTokenRouter, LaunchPacker
+
+    say("case router + packer end to end")
+    cfg = gen.get_config("test_medium_bf16")
+    T = gen.tokens_per_tile(cfg)
+    weights = gen.make_weights(cfg, seed=0)
+    requests = [[1, 2, 1], [1], [2, 1, 1, 1], [1, 3]]  # tiles per image
+    n_tiles = sum(sum(r) for r in requests)
+    px = gen.make_pixels(cfg, n_tiles, seed=1)
+    first_tile, t0 = {}, 0
+    for rid, tiles in enumerate(requests):
+        for k, n in enumerate(tiles):
+            first_tile[(rid, k)] = t0
+            t0 += n
+    router, packers = ImageTokenRouter(2, T), [LaunchPacker(), LaunchPacker()]
+    for rid, tiles in enumerate(requests):
+        for k, inst in enumerate(router.route(tiles)):
+            packers[inst].push(rid, k, tiles[k])
+    assert len(packers[0]) and len(packers[1])  # the load really is split
+    enc = V.VitEncoder(cfg, weights, device=0)
+    wparsed = O.unpack_weights(cfg, weights, np.float64)
+    seen = 0
+    for inst, p in enumerate(packers):
+        while len(p):
+            items, ipr, to = p.next_launch(max_images=3)
+            sel = np.concatenate([np.arange(first_tile[(i.request_id, i.image_index)],
+                                            first_tile[(i.request_id, i.image_index)] + i.tiles) for i in items])
+            out, rto = enc.encode(torch.from_numpy(px[sel]).cuda(), ipr, to)
+            torch.cuda.synchronize()
+            got = out.float().cpu().numpy()
+            assert rto[-1] == got.shape[0] == int(to[-1]) * T and len(rto) == len(ipr) + 1
+            for j, it in enumerate(items):
+                a = first_tile[(it.request_id, it.image_index)]
+                want, _ = O.vit_oracle_encode(cfg, wparsed, px[a:a + it.tiles], [1], np.asarray([0, it.tiles]))
+                assert_parity(got[int(to[j]) * T:int(to[j + 1]) * T], want, cfg["dtype"],
+                              f"instance {inst} request {it.request_id} image {it.image_index}")
+                router.complete(inst, it.tiles)
+                seen += 1
+    enc.close()
+    assert seen == sum(len(r) for r in requests) and router.pending == [0, 0]
