@@ -54,6 +54,8 @@ CONFIGS = {
     # several key tiles per segment and a ragged tail: 15x15 + 1 = 226 tokens per tile
     "test_medium_bf16": _cfg(210, 14, 256, 4, 512, 2, layers_global=1, proj_dims=(256, 128)),
     "test_medium_fp32": _cfg(210, 14, 256, 4, 512, 2, layers_global=1, proj_dims=(256, 128), dtype="fp32"),
+    # odd numbers of 64-wide k-stages (1, 3, 5) and one, two and three tile columns: 14x14 + 1 = 197 tokens
+    "test_oddk_bf16": _cfg(56, 4, 192, 3, 320, 2),
 }
 
 

@@ -53,6 +53,18 @@ def test_wide_batch_reaches_persistent_gemm():
     assert got.shape[0] == 160 * 226
 
 
+def test_odd_k_stage_counts_and_narrow_column_bands_on_the_persistent_gemm():
+    """340 tiles x 197 tokens = 66 980 rows (262 row blocks), so even the products with a single tile column
+    take the persistent kernel.  K = 64, 192 and 320 are 1, 3 and 5 k-stages: the two LDS stages change roles
+    from one tile to the next.  N = 576, 192 and 320 are three, one and two tile columns: a band with an idle
+    column and the 32 x 1 and 16 x 2 tile groups."""
+    cfg = gen.get_config("test_oddk_bf16")
+    tpi = [1] * 340
+    say("case odd k-stage counts (340 tiles, persistent GEMM)")
+    got, _ = check_case(cfg, tpi, [len(tpi)], images=[0, 171, 339], label="oddk")
+    assert got.shape[0] == 340 * 197
+
+
 def test_packing_invariance_on_gpu():
     """Reordering images / re-splitting requests must not change an image's tokens (beyond parity)."""
     cfg = gen.get_config("test_medium_bf16")
