@@ -29,7 +29,8 @@ typedef enum {
   VIT_EINVAL = -1,    /* bad argument or inconsistent shapes; nothing was launched        */
   VIT_ENOMEM = -2,    /* host or device allocation failed (create only)                   */
   VIT_ECAPACITY = -3, /* output or workspace buffer too small; nothing was launched       */
-  VIT_EDEVICE = -4    /* a HIP call failed; vit_last_error() carries the HIP error string */
+  VIT_EDEVICE = -4,   /* a HIP call failed; vit_last_error() carries the HIP error string */
+  VIT_ENOTREADY = -5  /* hand-off: not every image of the request has been published yet   */
 } vit_status_t;
 
 enum { VIT_DTYPE_FP32 = 0, VIT_DTYPE_BF16 = 1 };
@@ -143,6 +144,40 @@ enum {
 };
 vit_status_t vit_profile_enable(vit_encoder_t* enc, int enable);
 vit_status_t vit_profile_read(vit_encoder_t* enc, double* ms, int64_t* launches);
+
+/*
+ * Pull-style hand-off of finished image tokens (paper Sec. 4.3, "Image Token Transfer": the
+ * transfer is deferred until all image tokens of a request are ready; the consumer then pulls
+ * them from the producers' addresses).  Host-side table of device pointers and events; the
+ * only device work is the copy queued by vit_handoff_pull.  All functions are thread-safe.
+ *
+ *   vit_handoff_expect   announces request `request_id` with n_images (> 0) images.
+ *   vit_handoff_publish  image `image_index` of the request lies at `tokens` (device memory,
+ *                        `bytes` > 0 long) once the work queued so far on `stream` (hipStream_t;
+ *                        NULL = null stream) has finished: an event is recorded there.  The
+ *                        memory stays the producer's; it must stay valid and unchanged until
+ *                        vit_handoff_release and until any pull that was queued has run.
+ *   vit_handoff_complete 1 when every image has been published (device work may still be in
+ *                        flight), else 0; writes the byte total so far to *total_bytes if not NULL.
+ *   vit_handoff_pull     queues on `stream` the copies of all images' tokens, in image order,
+ *                        packed back to back into `dst` (device, `capacity` bytes), each behind
+ *                        its producer's event; the host does not wait.  *bytes (may be NULL)
+ *                        receives the total.  VIT_ENOTREADY if an image is missing,
+ *                        VIT_ECAPACITY if dst is too small; nothing is queued then.
+ *   vit_handoff_release  forgets the request and destroys its events.
+ * Errors: VIT_EINVAL for NULL / unknown request / index out of range / duplicate publish or
+ * expect, VIT_ENOMEM, VIT_EDEVICE.  `device` is made current by publish and pull.
+ */
+typedef struct vit_handoff vit_handoff_t; /* opaque; owned by the library */
+vit_status_t vit_handoff_create(int device, vit_handoff_t** out);
+void vit_handoff_destroy(vit_handoff_t* h); /* NULL allowed; pending pulls must have run */
+vit_status_t vit_handoff_expect(vit_handoff_t* h, int64_t request_id, int32_t n_images);
+vit_status_t vit_handoff_publish(vit_handoff_t* h, int64_t request_id, int32_t image_index, const void* tokens,
+                                 size_t bytes, void* stream);
+int32_t vit_handoff_complete(vit_handoff_t* h, int64_t request_id, size_t* total_bytes);
+vit_status_t vit_handoff_pull(vit_handoff_t* h, int64_t request_id, void* dst, size_t capacity, void* stream,
+                              size_t* bytes);
+vit_status_t vit_handoff_release(vit_handoff_t* h, int64_t request_id);
 
 /*
  * Measurement aid (no part of the encode path): runs a register-only bf16 MFMA loop

@@ -4,6 +4,7 @@ The binding marshals arguments only; every step of the encoder runs inside the H
 library.  PyTorch supplies device memory and the stream.
 """
 from .binding import (  # noqa: F401
+    TokenHandoff,
     VitEncoder,
     VitError,
     lib_path,

@@ -58,6 +58,20 @@ def load_library():
     lib.vit_encoder_destroy.argtypes = [C.c_void_p]
     lib.vit_profile_enable.restype = C.c_int
     lib.vit_profile_enable.argtypes = [C.c_void_p, C.c_int]
+    lib.vit_handoff_create.restype = C.c_int
+    lib.vit_handoff_create.argtypes = [C.c_int, C.POINTER(C.c_void_p)]
+    lib.vit_handoff_destroy.restype = None
+    lib.vit_handoff_destroy.argtypes = [C.c_void_p]
+    lib.vit_handoff_expect.restype = C.c_int
+    lib.vit_handoff_expect.argtypes = [C.c_void_p, C.c_int64, C.c_int32]
+    lib.vit_handoff_publish.restype = C.c_int
+    lib.vit_handoff_publish.argtypes = [C.c_void_p, C.c_int64, C.c_int32, C.c_void_p, C.c_size_t, C.c_void_p]
+    lib.vit_handoff_complete.restype = C.c_int32
+    lib.vit_handoff_complete.argtypes = [C.c_void_p, C.c_int64, C.POINTER(C.c_size_t)]
+    lib.vit_handoff_pull.restype = C.c_int
+    lib.vit_handoff_pull.argtypes = [C.c_void_p, C.c_int64, C.c_void_p, C.c_size_t, C.c_void_p, C.POINTER(C.c_size_t)]
+    lib.vit_handoff_release.restype = C.c_int
+    lib.vit_handoff_release.argtypes = [C.c_void_p, C.c_int64]
     lib.vit_mfma_ceiling.restype = C.c_int
     lib.vit_mfma_ceiling.argtypes = [C.c_int, C.c_double, C.POINTER(C.c_double)]
     lib.vit_profile_read.restype = C.c_int
@@ -127,6 +141,49 @@ def vit_mfma_ceiling(device: int = 0, seconds: float = 0.1) -> float:
 
 def vit_encoder_destroy(handle: int) -> None:
     load_library().vit_encoder_destroy(handle)
+
+
+class TokenHandoff:
+    """Pull-style hand-off table (argument marshalling over the vit_handoff_* calls).  Pointers and
+    streams are raw integers (torch: tensor.data_ptr(), torch.cuda.current_stream().cuda_stream)."""
+
+    def __init__(self, device: int = 0):
+        h = C.c_void_p()
+        _check(load_library().vit_handoff_create(int(device), C.byref(h)))
+        self._h = h
+
+    def close(self):
+        if self._h:
+            load_library().vit_handoff_destroy(self._h)
+            self._h = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+    def expect(self, request_id: int, n_images: int):
+        _check(load_library().vit_handoff_expect(self._h, request_id, n_images))
+
+    def publish(self, request_id: int, image_index: int, ptr: int, nbytes: int, stream: int = 0):
+        _check(load_library().vit_handoff_publish(self._h, request_id, image_index, C.c_void_p(ptr), nbytes,
+                                                  C.c_void_p(stream)))
+
+    def complete(self, request_id: int):
+        """(all images published?, bytes published so far)"""
+        n = C.c_size_t(0)
+        done = load_library().vit_handoff_complete(self._h, request_id, C.byref(n))
+        return bool(done), int(n.value)
+
+    def pull(self, request_id: int, dst_ptr: int, capacity: int, stream: int = 0) -> int:
+        n = C.c_size_t(0)
+        _check(load_library().vit_handoff_pull(self._h, request_id, C.c_void_p(dst_ptr), capacity, C.c_void_p(stream),
+                                               C.byref(n)))
+        return int(n.value)
+
+    def release(self, request_id: int):
+        _check(load_library().vit_handoff_release(self._h, request_id))
 
 
 # ---- convenience wrapper: torch tensors for device memory and the stream ----------------

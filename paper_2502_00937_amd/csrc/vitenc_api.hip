@@ -27,6 +27,21 @@ vit_status_t fail(vit_status_t st, const char* fmt, ...) {
   return st;
 }
 
+}  // namespace
+
+namespace vitenc {
+// the same per-thread message buffer for the other translation units of the library
+vit_status_t set_error(vit_status_t st, const char* fmt, ...) {
+  va_list ap;
+  va_start(ap, fmt);
+  vsnprintf(g_err, sizeof(g_err), fmt, ap);
+  va_end(ap);
+  return st;
+}
+}  // namespace vitenc
+
+namespace {
+
 #define HIP_TRY(expr)                                                                       \
   do {                                                                                      \
     hipError_t e_ = (expr);                                                                 \

@@ -234,3 +234,61 @@ def test_routed_and_packed_launches_match_the_oracle_per_request():
                 seen += 1
     enc.close()
     assert seen == sum(len(r) for r in requests) and router.pending == [0, 0]
+
+
+@pytest.mark.gpu
+def test_pull_style_handoff_assembles_a_request_encoded_in_two_launches():
+    """A request of four images is encoded in two launches (images 0, 2 and images 1, 3, as a router
+    might split it) interleaved with another request; the consumer pulls when all four are published
+    and must get exactly what one launch of the whole request produces, in image order."""
+    import torch
+
+    import paper_2502_00937_amd as V
+
+    say("case pull-style hand-off")
+    cfg = gen.get_config("test_medium_bf16")
+    T = gen.tokens_per_tile(cfg)
+    weights = gen.make_weights(cfg, seed=0)
+    tiles = [1, 2, 1, 3]                                  # tiles per image of request 5
+    to_all = np.concatenate([[0], np.cumsum(tiles)]).astype(np.int32)
+    px = torch.from_numpy(gen.make_pixels(cfg, int(to_all[-1]) + 2, seed=1)).cuda()  # + a 2-tile image of request 6
+    enc = V.VitEncoder(cfg, weights, device=0)
+    whole, _ = enc.encode(px[:int(to_all[-1])], [4], to_all)
+    torch.cuda.synchronize()
+
+    h = V.TokenHandoff(0)
+    h.expect(5, 4)
+    h.expect(6, 1)
+    side = torch.cuda.Stream()
+    outs = []
+    other = torch.arange(int(to_all[-1]), int(to_all[-1]) + 2)
+    for launch, imgs in enumerate([[0, 2], [1, 3]]):
+        sel = torch.cat([torch.arange(int(to_all[i]), int(to_all[i + 1])) for i in imgs] + ([other] if launch == 0 else []))
+        n = [tiles[i] for i in imgs] + ([2] if launch == 0 else [])
+        ipr = [1] * len(n)
+        to = np.concatenate([[0], np.cumsum(n)]).astype(np.int32)
+        with torch.cuda.stream(side):
+            out, _ = enc.encode(px[sel.cuda()].contiguous(), ipr, to)
+            outs.append(out)                               # producer memory stays alive until release
+            for j, i in enumerate(imgs):
+                rows = out[int(to[j]) * T:int(to[j + 1]) * T]
+                h.publish(5, i, rows.data_ptr(), rows.numel() * rows.element_size(), side.cuda_stream)
+            if launch == 0:
+                rows = out[int(to[2]) * T:int(to[3]) * T]
+                h.publish(6, 0, rows.data_ptr(), rows.numel() * rows.element_size(), side.cuda_stream)
+                assert h.complete(5)[0] is False and h.complete(6)[0] is True
+                with pytest.raises(V.VitError):
+                    h.pull(5, whole.data_ptr(), 1 << 30, 0)  # not ready: nothing is queued
+    done, nbytes = h.complete(5)
+    assert done and nbytes == whole.numel() * whole.element_size()
+    dst = torch.empty_like(whole)
+    with pytest.raises(V.VitError):
+        h.pull(5, dst.data_ptr(), nbytes - 1, torch.cuda.current_stream().cuda_stream)  # too small
+    got = h.pull(5, dst.data_ptr(), nbytes, torch.cuda.current_stream().cuda_stream)  # waits on `side` through the events
+    torch.cuda.synchronize()
+    assert got == nbytes
+    assert torch.equal(dst.view(torch.int16), whole.view(torch.int16))  # bitwise: packing never changes an image's tokens
+    h.release(5)
+    h.release(6)
+    h.close()
+    enc.close()

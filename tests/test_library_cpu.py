@@ -99,3 +99,33 @@ def test_product_does_not_import_oracle():
             if f.endswith((".py", ".hip", ".h", ".cpp")):
                 src = open(os.path.join(dirpath, f)).read()
                 assert "oracle" not in src.lower(), os.path.join(dirpath, f)
+
+
+def test_handoff_table_logic_without_a_device():
+    """Everything the hand-off decides before it touches HIP: unknown / duplicate requests, missing
+    images, NULL arguments (publish itself needs a device for its event)."""
+    h = V.TokenHandoff(0)
+    h.expect(7, 3)
+    with pytest.raises(V.VitError) as e:
+        h.expect(7, 1)
+    assert e.value.status == -1 and "already known" in str(e.value)
+    with pytest.raises(V.VitError):
+        h.expect(8, 0)
+    assert h.complete(7) == (False, 0)
+    assert h.complete(99) == (False, 0)
+    with pytest.raises(V.VitError) as e:
+        h.pull(7, 4096, 1 << 20)
+    assert e.value.status == -5 and "0 of 3 images" in str(e.value)  # VIT_ENOTREADY
+    with pytest.raises(V.VitError) as e:
+        h.pull(99, 4096, 1 << 20)
+    assert e.value.status == -1
+    with pytest.raises(V.VitError):
+        h.publish(99, 0, 4096, 16)          # unknown request
+    with pytest.raises(V.VitError):
+        h.publish(7, 3, 4096, 16)           # image index out of range
+    with pytest.raises(V.VitError):
+        h.publish(7, 0, 0, 16)              # NULL tokens
+    h.release(7)
+    with pytest.raises(V.VitError):
+        h.release(7)
+    h.close()
