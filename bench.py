@@ -222,7 +222,9 @@ def main():
         result["roofline"] = {
             "bound": "mfma", "kernel": "gemm_bf16_dma_kernel (all matrix products of one step)",
             "achieved": achieved, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": achieved / PEAK_BF16_TFLOPS,
-            "measured_mfma_ceiling": V.vit_mfma_ceiling(0, 0.1),  # register-only MFMA loop on this device, TFLOP/s
+            # register-only MFMA loop on this device, TFLOP/s: operands random like real data / one constant
+            "measured_mfma_ceiling": V.vit_mfma_ceiling(0, 0.1, True),
+            "measured_mfma_ceiling_constant_operands": V.vit_mfma_ceiling(0, 0.1, False),
             "traffic": GEMM_TRAFFIC_BYTES_PER_STEP.get(args.workload), "traffic_unit": "bytes per step (all launches), rocprofv3 --pmc",
             "launches_per_step": int(gemm_n), "ms_per_step": gemm_ms,
             "avg_launch_ms": gemm_ms / max(gemm_n, 1), "flop_per_step": gemm_f,

@@ -183,12 +183,15 @@ vit_status_t vit_handoff_release(vit_handoff_t* h, int64_t request_id);
  * Measurement aid (no part of the encode path): runs a register-only bf16 MFMA loop
  * (v_mfma_f32_32x32x16_bf16, two waves per SIMD, no memory traffic) on `device` for about
  * `seconds` (0 < seconds <= 2) on the null stream and writes the sustained rate in TFLOP/s
- * to *tflops (host pointer).  This is the practical ceiling of the matrix cores on the
- * device at hand, printed by the benchmark beside the nominal peak that every reported
- * fraction uses.  Allocates and frees 1 KiB of device memory; synchronises the device's
- * null stream.  Errors: VIT_EINVAL (NULL / range), VIT_EDEVICE.
+ * to *tflops (host pointer).  random_operands != 0: the operands are seeded uniform [-1, 1)
+ * values, as the products of the encoder have; 0: one constant.  The chip is power-limited
+ * and the clock it holds depends on the operand data, so the two differ widely; the random
+ * figure is the practical ceiling of the matrix cores for real data, printed by the
+ * benchmark beside the nominal peak that every reported fraction uses.  Allocates and frees
+ * 65 KiB of device memory; synchronises the device's null stream.
+ * Errors: VIT_EINVAL (NULL / range), VIT_EDEVICE.
  */
-vit_status_t vit_mfma_ceiling(int device, double seconds, double* tflops);
+vit_status_t vit_mfma_ceiling(int device, double seconds, int32_t random_operands, double* tflops);
 
 #pragma GCC visibility pop
 #ifdef __cplusplus

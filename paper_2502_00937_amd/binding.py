@@ -73,7 +73,7 @@ def load_library():
     lib.vit_handoff_release.restype = C.c_int
     lib.vit_handoff_release.argtypes = [C.c_void_p, C.c_int64]
     lib.vit_mfma_ceiling.restype = C.c_int
-    lib.vit_mfma_ceiling.argtypes = [C.c_int, C.c_double, C.POINTER(C.c_double)]
+    lib.vit_mfma_ceiling.argtypes = [C.c_int, C.c_double, C.c_int32, C.POINTER(C.c_double)]
     lib.vit_profile_read.restype = C.c_int
     lib.vit_profile_read.argtypes = [C.c_void_p, C.POINTER(C.c_double), C.POINTER(C.c_int64)]
     _LIB = lib
@@ -132,10 +132,10 @@ def vit_encode_packed(handle: int, pixels_ptr: int, images_per_request, tile_off
     return rto
 
 
-def vit_mfma_ceiling(device: int = 0, seconds: float = 0.1) -> float:
+def vit_mfma_ceiling(device: int = 0, seconds: float = 0.1, random_operands: bool = True) -> float:
     """Sustained TFLOP/s of a register-only bf16 MFMA loop on `device` (measurement aid)."""
     out = C.c_double(0.0)
-    _check(load_library().vit_mfma_ceiling(int(device), float(seconds), C.byref(out)))
+    _check(load_library().vit_mfma_ceiling(int(device), float(seconds), 1 if random_operands else 0, C.byref(out)))
     return out.value
 
 

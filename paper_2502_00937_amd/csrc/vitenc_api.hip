@@ -229,21 +229,24 @@ struct ProfScope {
   }
 };
 
-// Register-only MFMA loop: eight independent 32x32 accumulators per wave, no memory traffic.  What it
-// sustains is the matrix cores' practical ceiling on this device (the clock the chip holds under
-// full MFMA load times the issue rate), the yardstick beside the nominal peak.
-__global__ __launch_bounds__(256) void mfma_ceiling_kernel(float* out, int iters) {
-  bf16x8 a, b;
-  for (int i = 0; i < 8; ++i) {
-    a[i] = (__bf16)(0.001f * (float)(threadIdx.x + i));
-    b[i] = (__bf16)(0.002f * (float)(threadIdx.x % 7 + i));
+// Register-only MFMA loop: eight independent 32x32 accumulators per wave, no memory traffic inside the
+// loop.  What it sustains is the matrix cores' practical ceiling on this device: the clock the chip
+// holds under full MFMA load times the issue rate.  That clock depends on the operand DATA (the chip
+// is power-limited and random mantissas toggle far more of the multiplier array than constants do:
+// about 1.75 PFLOP/s against 2.48 measured), so the operands are four fragments per matrix of
+// caller-supplied values, here seeded uniform [-1, 1), as a matrix product of real activations has.
+__global__ __launch_bounds__(256) void mfma_ceiling_kernel(const u32x4* __restrict__ frag, float* out, int iters) {
+  bf16x8 a[4], b[4];
+  for (int i = 0; i < 4; ++i) {
+    a[i] = __builtin_bit_cast(bf16x8, frag[(threadIdx.x * 8 + i) & 4095]);
+    b[i] = __builtin_bit_cast(bf16x8, frag[(threadIdx.x * 8 + 4 + i) & 4095]);
   }
   f32x16 acc[8];
   for (int j = 0; j < 8; ++j)
     for (int v = 0; v < 16; ++v) acc[j][v] = 0.f;
   for (int it = 0; it < iters; ++it) {
 #pragma unroll
-    for (int j = 0; j < 8; ++j) acc[j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, acc[j], 0, 0, 0);
+    for (int j = 0; j < 8; ++j) acc[j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[j & 3], b[(j >> 1) & 3], acc[j], 0, 0, 0);
   }
   float sum = 0.f;
   for (int j = 0; j < 8; ++j)
@@ -621,15 +624,24 @@ vit_status_t vit_profile_read(vit_encoder_t* e, double* ms, int64_t* launches) {
   return VIT_OK;
 }
 
-vit_status_t vit_mfma_ceiling(int device, double seconds, double* tflops) {
+vit_status_t vit_mfma_ceiling(int device, double seconds, int32_t random_operands, double* tflops) {
   if (!tflops || !(seconds > 0.0) || seconds > 2.0) return fail(VIT_EINVAL, "vit_mfma_ceiling: bad argument");
   HIP_TRY(hipSetDevice(device));
   int n_cu = 0;
   HIP_TRY(hipDeviceGetAttribute(&n_cu, hipDeviceAttributeMultiprocessorCount, device));
-  float* out = nullptr;
-  HIP_TRY(hipMalloc(&out, 256 * sizeof(float)));
+  // 4096 fragments of 8 bf16: seeded uniform [-1, 1) (xorshift32) or the constant 1/128
+  std::vector<uint16_t> host(4096 * 8);
+  uint32_t rs = 0x9E3779B9u;
+  for (auto& v : host) {
+    rs ^= rs << 13; rs ^= rs >> 17; rs ^= rs << 5;
+    v = random_operands ? f32_to_bf16((float)(rs >> 8) * (2.0f / 16777216.0f) - 1.0f) : (uint16_t)0x3C00;
+  }
+  unsigned char* dev = nullptr;
+  HIP_TRY(hipMalloc((void**)&dev, host.size() * 2 + 1024));
+  hipError_t err = hipMemcpy(dev, host.data(), host.size() * 2, hipMemcpyHostToDevice);
+  float* out = (float*)(dev + host.size() * 2);
   hipEvent_t e0 = nullptr, e1 = nullptr;
-  hipError_t err = hipEventCreate(&e0);
+  if (err == hipSuccess) err = hipEventCreate(&e0);
   if (err == hipSuccess) err = hipEventCreate(&e1);
   const int grid = 2 * n_cu;  // 4 waves per workgroup, 2 workgroups per unit: two waves per SIMD
   const double flop_per_iter = (double)grid * 4 * 8 * 2.0 * 32 * 32 * 16;
@@ -638,7 +650,7 @@ vit_status_t vit_mfma_ceiling(int device, double seconds, double* tflops) {
   for (int rep = 0; rep < 2 && err == hipSuccess; ++rep) {
     err = hipEventRecord(e0, 0);
     if (err != hipSuccess) break;
-    hipLaunchKernelGGL(mfma_ceiling_kernel, dim3(grid), dim3(256), 0, 0, out, iters);
+    hipLaunchKernelGGL(mfma_ceiling_kernel, dim3(grid), dim3(256), 0, 0, (const u32x4*)dev, out, iters);
     err = hipGetLastError();
     if (err == hipSuccess) err = hipEventRecord(e1, 0);
     if (err == hipSuccess) err = hipEventSynchronize(e1);
@@ -651,7 +663,7 @@ vit_status_t vit_mfma_ceiling(int device, double seconds, double* tflops) {
   }
   if (e0) (void)hipEventDestroy(e0);
   if (e1) (void)hipEventDestroy(e1);
-  (void)hipFree(out);
+  (void)hipFree(dev);
   if (err != hipSuccess) return fail(VIT_EDEVICE, "vit_mfma_ceiling: %s", hipGetErrorString(err));
   *tflops = best;
   return VIT_OK;

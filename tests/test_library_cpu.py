@@ -34,9 +34,9 @@ def test_mfma_ceiling_rejects_bad_arguments_before_touching_a_device():
 
     lib = V.load_library()
     out = C.c_double(-1.0)
-    assert lib.vit_mfma_ceiling(0, 0.1, None) == -1      # VIT_EINVAL: NULL result pointer
-    assert lib.vit_mfma_ceiling(0, 0.0, C.byref(out)) == -1
-    assert lib.vit_mfma_ceiling(0, 5.0, C.byref(out)) == -1
+    assert lib.vit_mfma_ceiling(0, 0.1, 1, None) == -1      # VIT_EINVAL: NULL result pointer
+    assert lib.vit_mfma_ceiling(0, 0.0, 1, C.byref(out)) == -1
+    assert lib.vit_mfma_ceiling(0, 5.0, 0, C.byref(out)) == -1
     assert out.value == -1.0
 
 
