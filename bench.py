@@ -26,7 +26,7 @@ HBM_PEAK_GBS = 8000.0
 # HBM-side bytes of all matrix-product launches of ONE cfg3 step, from the two rocprofv3 --pmc runs
 # (FETCH_SIZE x 2.0 + WRITE_SIZE x 1.0, factors from the copy calibration) summarised in
 # profiles/kernels_cfg3_ragged_hbm_traffic.md.  A profile figure, not measured by this script.
-GEMM_TRAFFIC_BYTES_PER_STEP = {"cfg3": 258.3e9}
+GEMM_TRAFFIC_BYTES_PER_STEP = {"cfg3": 257.9e9}
 
 
 def flops(cfg, tile_offsets):
