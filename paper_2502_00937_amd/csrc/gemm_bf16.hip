@@ -306,13 +306,16 @@ __device__ __forceinline__ void wave_epilogue_p(const GemmArgs& a, f32x16 (&acc)
     // Pieces of 16 rows x 32 fp32 columns (128 bytes + pad per staged row); a piece is read back
     // as 8 lanes per row, 8 rows per pass.  The residual values of a 32 x 32 unit (2 pieces of
     // 2 passes) are loaded one unit ahead so their latency hides behind the previous unit.
+    // Addresses are a wave-uniform base (scalar arithmetic) plus a per-lane byte offset that never
+    // changes; the bounds tests compare a per-lane limit with a compile-time row / column.
     const int sr0 = lane >> 3, sc = (lane & 7) * 4;
+    const uint32_t lane_off = (uint32_t)(sr0 * a.ldo + sc) * 4u;
+    unsigned char* const tile_base = (unsigned char*)a.resid + ((size_t)row0 * a.ldo + ncol0) * 4;
+    const int row_lim = a.M - row0 - sr0, col_lim = a.N - ncol0 - sc;  // valid: row offset < row_lim, col offset < col_lim
     auto x_ptr = [&](int i, int j, int half, int p) {
-      return a.resid + (size_t)(row0 + i * 32 + half * 16 + p * 8 + sr0) * a.ldo + ncol0 + j * 32 + sc;
+      return (float*)(tile_base + ((size_t)(i * 32 + half * 16 + p * 8) * a.ldo + j * 32) * 4 + lane_off);
     };
-    auto x_ok = [&](int i, int j, int half, int p) {
-      return row0 + i * 32 + half * 16 + p * 8 + sr0 < a.M && ncol0 + j * 32 + sc < a.N;
-    };
+    auto x_ok = [&](int i, int j, int half, int p) { return i * 32 + half * 16 + p * 8 < row_lim && j * 32 < col_lim; };
     f32x4 xin[2][2][2];  // [buffer][half][pass] of one (row block, column block) unit
     auto load_unit = [&](int u, int buf) {  // unit u = i * FN + j
       const int i = u / FN, j = u % FN;
@@ -350,6 +353,12 @@ __device__ __forceinline__ void wave_epilogue_p(const GemmArgs& a, f32x16 (&acc)
     }
   } else {  // EPI_BIAS, EPI_BIAS_GELU: bf16 output, pieces of 16 rows x 64 columns (128 bytes + pad)
     // (storing the 8-byte register quads directly was measured slower than this LDS round trip)
+    // Store addresses: wave-uniform base (scalar arithmetic) + a per-lane byte offset that never changes.
+    const int sc = (lane & 7) * 8;
+    const uint32_t lane_off = (uint32_t)((lane >> 3) * a.ldo + sc) * 2u;
+    unsigned char* const tile_base = (unsigned char*)a.out + ((size_t)row0 * a.ldo + ncol0) * 2;
+    const int row_lim = a.M - row0 - (lane >> 3);
+    const bool col_ok = ncol0 + sc < a.N;
 #pragma unroll
     for (int i = 0; i < FM; ++i) {
       u32x2 pk[FN][4];  // all lanes convert once; the two half-wave passes below only move data
@@ -377,10 +386,10 @@ __device__ __forceinline__ void wave_epilogue_p(const GemmArgs& a, f32x16 (&acc)
         __builtin_amdgcn_wave_barrier();
 #pragma unroll
         for (int p = 0; p < 2; ++p) {  // 8 lanes per row (8 bf16 each), 8 rows per pass
-          const int sr = p * 8 + (lane >> 3), sc = (lane & 7) * 8;
-          const int row = row0 + i * 32 + half * 16 + sr, col = ncol0 + sc;
+          const int sr = p * 8 + (lane >> 3);
           const u32x4 t = *(const u32x4*)(st + sr * D_STAGING_ROW + sc * 2);
-          if (row < a.M && col < a.N) *(u32x4*)((bf16_t*)a.out + (size_t)row * a.ldo + col) = t;
+          if (i * 32 + half * 16 + p * 8 < row_lim && col_ok)
+            *(u32x4*)(tile_base + (size_t)(i * 32 + half * 16 + p * 8) * a.ldo * 2 + lane_off) = t;
         }
         __builtin_amdgcn_wave_barrier();
       }
