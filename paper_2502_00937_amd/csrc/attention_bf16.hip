@@ -264,6 +264,10 @@ __global__ __launch_bounds__(64 * NW, QB == 1 ? (DHP == 64 ? 4 : DHP <= 96 ? 3 :
     }
     __syncthreads();
   };
+  // Every load issued so far (the Q fragments among them) has landed before the loop starts: the
+  // compiler's wait-count pass otherwise carries "Q may still be in flight" around the loop and makes
+  // each tile's first MFMAs wait for the global loads of the NEXT tile issued just before them.
+  __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0)
   const int n_full = w.seg_len / AKV;  // tiles with all 64 keys valid
   for (int t = 0; t < n_full; ++t) process_tile(t, std::false_type{});
   if (n_full < n_tiles) process_tile(n_full, std::true_type{});
