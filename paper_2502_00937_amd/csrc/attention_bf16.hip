@@ -70,6 +70,7 @@ __global__ __launch_bounds__(64 * NW, QB == 1 ? (DHP == 64 ? 4 : DHP <= 96 ? 3 :
   const int head = blockIdx.y;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int lq = lane & 31, g = lane >> 5;
+  const int partner_addr = (lane ^ 32) << 2;  // ds_bpermute byte address of the lane that holds the other 16 keys of a query
   const bf16_t* base = (const bf16_t*)a.qkv;
   const int qoff = head * DHP, koff = (a.heads + head) * DHP, voff = (2 * a.heads + head) * DHP;
   const int seg_end = w.seg_start + w.seg_len;
@@ -212,7 +213,7 @@ __global__ __launch_bounds__(64 * NW, QB == 1 ? (DHP == 64 ? 4 : DHP <= 96 ? 3 :
         float mx = st[qb][0];
 #pragma unroll
         for (int v = 1; v < 16; ++v) mx = fmaxf(mx, st[qb][v]);
-        mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
+        mx = fmaxf(mx, __builtin_bit_cast(float, __builtin_amdgcn_ds_bpermute(partner_addr, __builtin_bit_cast(int, mx))));
         // The reference maximum m only has to keep exp2 in range, not to be the exact running
         // maximum: it moves (and the accumulators are rescaled) only when some query's logits
         // outgrow it by more than 2^RESCALE_SLACK, so p <= 2^RESCALE_SLACK instead of p <= 1.
