@@ -103,38 +103,48 @@ __global__ __launch_bounds__(64 * NW, QB == 1 ? (DHP == 64 ? 4 : DHP <= 96 ? 3 :
   // logits are masked, the clamped values only need to be finite).
   const unsigned char* seg_base = (const unsigned char*)(base + (size_t)w.seg_start * a.ld_qkv);
   const uint32_t row_bytes = (uint32_t)a.ld_qkv * 2u;
-  int k_key[Sh::K_PER], v_kp[Sh::V_PER];
-  uint32_t k_col[Sh::K_PER], v_col[Sh::V_PER];
+  // Each thread's (row, column) inside a tile is fixed: its byte offsets from the tile's first row are
+  // computed once, and a full tile is loaded from a wave-uniform base plus those offsets with no
+  // address arithmetic at all.  Only a segment's last, partial tile clamps rows past the end to the
+  // last row (their logits are masked, the clamped values only need to be finite).
+  uint32_t k_off[Sh::K_PER], v_off[Sh::V_PER];
 #pragma unroll
+  // (threads whose item index lies past the tile's last item load the last item again and do not
+  //  store it: no load sits under divergent control flow)
   for (int i = 0; i < Sh::K_PER; ++i) {
-    const int it = tid + i * ANT;
-    k_key[i] = it / Sh::NCH;
-    k_col[i] = (uint32_t)(koff + (it - k_key[i] * Sh::NCH) * 8) * 2u;
+    const int it = min(tid + i * ANT, Sh::K_ITEMS - 1), key = it / Sh::NCH;
+    k_off[i] = (uint32_t)key * row_bytes + (uint32_t)(koff + (it - key * Sh::NCH) * 8) * 2u;
   }
 #pragma unroll
   for (int i = 0; i < Sh::V_PER; ++i) {
-    const int it = tid + i * ANT;
-    v_kp[i] = it & 31;
-    v_col[i] = (uint32_t)(voff + (it >> 5) * 8) * 2u;
+    const int it = min(tid + i * ANT, Sh::V_ITEMS - 1);
+    v_off[i] = (uint32_t)(2 * (it & 31)) * row_bytes + (uint32_t)(voff + (it >> 5) * 8) * 2u;
   }
-  auto load_tile = [&](int k0) {
+  auto load_tile = [&](int k0, auto partial_tag) {
+    constexpr bool PARTIAL = decltype(partial_tag)::value;
+    const unsigned char* tile_base = seg_base + (size_t)k0 * row_bytes;  // wave-uniform
     const int last = w.seg_len - 1 - k0;  // largest valid row index inside this tile (>= 0)
 #pragma unroll
     for (int i = 0; i < Sh::K_PER; ++i) {
-      const int it = tid + i * ANT;
-      if (Sh::K_ITEMS % ANT == 0 || it < Sh::K_ITEMS) {
-        const uint32_t row = (uint32_t)(k0 + min(k_key[i], last));
-        rk[i] = *(const u32x4*)(seg_base + (size_t)row * row_bytes + k_col[i]);
+      const int it = min(tid + i * ANT, Sh::K_ITEMS - 1);
+      uint32_t off = k_off[i];
+      if (PARTIAL) {
+        const int key = it / Sh::NCH;
+        off -= (uint32_t)(key - min(key, last)) * row_bytes;
       }
+      rk[i] = *(const u32x4*)(tile_base + off);
     }
 #pragma unroll
     for (int i = 0; i < Sh::V_PER; ++i) {
-      const int it = tid + i * ANT;
-      if (Sh::V_ITEMS % ANT == 0 || it < Sh::V_ITEMS) {
-        const uint32_t r0 = (uint32_t)(k0 + min(2 * v_kp[i], last)), r1 = (uint32_t)(k0 + min(2 * v_kp[i] + 1, last));
-        rv0[i] = *(const u32x4*)(seg_base + (size_t)r0 * row_bytes + v_col[i]);
-        rv1[i] = *(const u32x4*)(seg_base + (size_t)r1 * row_bytes + v_col[i]);
+      const int it = min(tid + i * ANT, Sh::V_ITEMS - 1);
+      uint32_t o0 = v_off[i], o1 = v_off[i] + row_bytes;
+      if (PARTIAL) {
+        const int r = 2 * (it & 31);
+        o0 -= (uint32_t)(r - min(r, last)) * row_bytes;
+        o1 -= (uint32_t)(r + 1 - min(r + 1, last)) * row_bytes;
       }
+      rv0[i] = *(const u32x4*)(tile_base + o0);
+      rv1[i] = *(const u32x4*)(tile_base + o1);
     }
   };
   // registers -> LDS; V is transposed on the way in: V^T[d][2kp], V^T[d][2kp+1] packed into one word
@@ -165,7 +175,8 @@ __global__ __launch_bounds__(64 * NW, QB == 1 ? (DHP == 64 ? 4 : DHP <= 96 ? 3 :
   const int n_tiles = (w.seg_len + AKV - 1) / AKV;
   // a wave whose 32 * QB query rows all lie past the segment end (last block of a segment) skips the arithmetic
   const bool wave_active = w.q0 + wave * QB * 32 < seg_end;
-  load_tile(0);
+  if (w.seg_len >= AKV) load_tile(0, std::false_type{});
+  else load_tile(0, std::true_type{});
   store_tile(lds, lds + Sh::K_BYTES);
   __syncthreads();
 
@@ -175,7 +186,10 @@ __global__ __launch_bounds__(64 * NW, QB == 1 ? (DHP == 64 ? 4 : DHP <= 96 ? 3 :
     constexpr bool MASK = decltype(mask_tag)::value;
     const unsigned char* sK = lds + (t & 1) * Sh::STAGE;
     const unsigned char* sVt = sK + Sh::K_BYTES;
-    if (t + 1 < n_tiles) load_tile((t + 1) * AKV);
+    if (t + 1 < n_tiles) {  // the next tile is full unless it is the segment's last, partial one
+      if ((t + 2) * AKV <= w.seg_len) load_tile((t + 1) * AKV, std::false_type{});
+      else load_tile((t + 1) * AKV, std::true_type{});
+    }
 
     const int remaining = w.seg_len - t * AKV;  // valid keys in this tile (may exceed AKV)
     // the tile is processed in two 32-key halves to keep S^T and P^T small in registers
