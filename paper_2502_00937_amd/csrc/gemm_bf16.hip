@@ -3,12 +3,12 @@
 // Both operands are K-contiguous, so a lane's 8 consecutive k values are one 16-byte
 // load and map directly onto the v_mfma_f32_32x32x16_bf16 operand registers.
 //
-// Two kernels share the fragment layout and the epilogues:
-// * gemm_bf16_kernel (below 256 tiles of 256 x 256): one 128 x 128 x 64 tile per workgroup, four
-//   waves of 64 x 64, operands staged global -> registers -> LDS with two LDS stages, one barrier
-//   per k-step, the loads of step k+1 in flight while step k is multiplied.
+// Two kernels share the fragment layout and the epilogues; both move their operands global -> LDS
+// directly (global_load_lds_dwordx4) and are described where they are defined:
+// * gemm_bf16_ring_kernel (below 256 tiles of 256 x 256): one 128 x 128 tile per workgroup, eight
+//   waves of 64 x 32, a ring of four 64-wide k-stages;
 // * gemm_bf16_dma_kernel (everything large): persistent, 256 x 256 tiles, eight waves of 128 x 64,
-//   operands global -> LDS directly; described where it is defined.
+//   two 64-wide k-stages.
 // * LDS tiles are [row][64 bf16] with the 16-byte chunks XOR-swizzled by (row >> 1) & 7:
 //   LDS serves a 16-byte-per-lane read 16 lanes at a time over 64 banks, and this
 //   swizzle makes any 16 consecutive rows of one logical chunk hit 16 distinct bank groups.
@@ -29,28 +29,6 @@ namespace {
 
 constexpr int BK = 64;  // bf16 elements per k-step = 128 bytes = 8 chunks of 16 bytes
 constexpr int GROUP_M = 8, GROUP_N = 4;
-
-__device__ __forceinline__ uint32_t lds_off(int row, int chunk) {
-  return (uint32_t)(row * 128 + ((chunk ^ ((row >> 1) & 7)) << 4));
-}
-
-// One k-step of a row-major tile: thread t moves 16-byte chunk (t & 7) of row (t >> 3) (+ NT/8 per pass).
-template <int LOADS, int NT>
-__device__ __forceinline__ void tile_load(u32x4 (&r)[LOADS], const bf16_t* base, int ld, int tid, int kt) {
-#pragma unroll
-  for (int i = 0; i < LOADS; ++i) {
-    const int idx = tid + i * NT, row = idx >> 3, ch = idx & 7;
-    r[i] = *(const u32x4*)(base + (size_t)row * ld + kt * BK + ch * 8);
-  }
-}
-template <int LOADS, int NT>
-__device__ __forceinline__ void tile_store(const u32x4 (&r)[LOADS], unsigned char* lds, int tid) {
-#pragma unroll
-  for (int i = 0; i < LOADS; ++i) {
-    const int idx = tid + i * NT, row = idx >> 3, ch = idx & 7;
-    *(u32x4*)(lds + lds_off(row, ch)) = r[i];
-  }
-}
 
 // Epilogue of one wave.  acc[i][j] is a transposed 32x32 block: the lane holds token row
 // row0 + 32i + (lane & 31); register 4jj + e holds output column ncol0 + 32j + 8jj + 4(lane >> 5) + e.
@@ -150,85 +128,6 @@ __device__ __forceinline__ void wave_epilogue(const GemmArgs& a, f32x16 (&acc)[F
       __builtin_amdgcn_wave_barrier();
     }
   }
-}
-
-template <int BM, int BN, int WM, int WN, int EPI>
-__global__ __launch_bounds__(WM* WN * 64) void gemm_bf16_kernel(const GemmArgs a, int tiles_m, int tiles_n,
-                                                               int mt_per_xcd, int n_bands) {
-  constexpr int NT = WM * WN * 64;
-  constexpr int TM = BM / WM, TN = BN / WN;  // per-wave tile
-  constexpr int FM = TM / 32, FN = TN / 32;  // 32x32 MFMA blocks per wave
-  constexpr int A_LOADS = BM * 8 / NT, B_LOADS = BN * 8 / NT;
-  static_assert(BM * 8 % NT == 0 && BN * 8 % NT == 0, "tile/threads mismatch");
-  static_assert(WM * WN * 32 * (TN * 4 + 16) <= 2 * (BM + BN) * 128, "epilogue staging must fit in the tile buffers");
-
-  extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
-  unsigned char* sA = smem;                 // 2 stages x BM x 128 B
-  unsigned char* sB = smem + 2 * BM * 128;  // 2 stages x BN x 128 B
-
-  // ---- tile assignment (see header comment)
-  const int xcd = blockIdx.x & 7, q = blockIdx.x >> 3;
-  const int blk = q / (GROUP_M * GROUP_N), r = q - blk * (GROUP_M * GROUP_N);
-  const int mb = blk / n_bands, nb = blk - mb * n_bands;
-  const int m_local = mb * GROUP_M + r / GROUP_N;
-  const int tile_m = xcd * mt_per_xcd + m_local, tile_n = nb * GROUP_N + (r % GROUP_N);
-  if (m_local >= mt_per_xcd || tile_m >= tiles_m || tile_n >= tiles_n) return;
-  const int m0 = tile_m * BM, n0 = tile_n * BN;
-
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  const int wm = wave / WN, wn = wave % WN;
-  const int lrow = lane & 31, lk = lane >> 5;
-
-  const bf16_t* A = (const bf16_t*)a.A + (size_t)m0 * a.lda;
-  const bf16_t* W = (const bf16_t*)a.W + (size_t)n0 * a.ldw;
-
-  u32x4 ra[A_LOADS], rb[B_LOADS];
-  f32x16 acc[FM][FN];
-#pragma unroll
-  for (int i = 0; i < FM; ++i)
-#pragma unroll
-    for (int j = 0; j < FN; ++j)
-#pragma unroll
-      for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
-
-  const int KT = a.K / BK;
-  tile_load<A_LOADS, NT>(ra, A, a.lda, tid, 0);
-  tile_load<B_LOADS, NT>(rb, W, a.ldw, tid, 0);
-  tile_store<A_LOADS, NT>(ra, sA, tid);
-  tile_store<B_LOADS, NT>(rb, sB, tid);
-  __syncthreads();
-
-  for (int kt = 0; kt < KT; ++kt) {
-    const int stage = kt & 1;
-    if (kt + 1 < KT) {
-      tile_load<A_LOADS, NT>(ra, A, a.lda, tid, kt + 1);
-      tile_load<B_LOADS, NT>(rb, W, a.ldw, tid, kt + 1);
-    }
-    const unsigned char* pa = sA + stage * BM * 128;
-    const unsigned char* pb = sB + stage * BN * 128;
-#pragma unroll
-    for (int ks = 0; ks < 4; ++ks) {
-      bf16x8 fa[FM], fb[FN];
-#pragma unroll
-      for (int i = 0; i < FM; ++i)
-        fa[i] = *(const bf16x8*)(pa + lds_off(wm * TM + i * 32 + lrow, ks * 2 + lk));
-#pragma unroll
-      for (int j = 0; j < FN; ++j)
-        fb[j] = *(const bf16x8*)(pb + lds_off(wn * TN + j * 32 + lrow, ks * 2 + lk));
-#pragma unroll
-      for (int i = 0; i < FM; ++i)
-#pragma unroll
-        for (int j = 0; j < FN; ++j)
-          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb[j], fa[i], acc[i][j], 0, 0, 0);
-    }
-    if (kt + 1 < KT) {
-      tile_store<A_LOADS, NT>(ra, sA + (stage ^ 1) * BM * 128, tid);
-      tile_store<B_LOADS, NT>(rb, sB + (stage ^ 1) * BN * 128, tid);
-    }
-    __syncthreads();
-  }
-
-  wave_epilogue<EPI, FM, FN>(a, acc, smem, m0 + wm * TM, n0 + wn * TN, wave, lane);
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -612,6 +511,141 @@ __global__ __launch_bounds__(512) void gemm_bf16_dma_kernel(const GemmArgs a, in
   }
 }
 
+// ---------------------------------------------------------------------------------------------
+// Small-problem kernel (fewer than 256 tiles of 256 x 256): one 128 x 128 tile per workgroup, eight
+// waves of 64 x 32 (two per SIMD), operands global -> LDS directly into a ring of four 64-wide
+// k-stages (32 KiB each).  Here a workgroup is alone on its compute unit and nothing but its own
+// instruction order hides latency: the loads run three k-stages ahead, one wait + barrier per
+// stage establishes that the stage has landed for every wave and that the slot refilled next is
+// dead, and all fragments of a stage are read before its MFMAs start (registers are plentiful
+// here).  (The register-staged predecessor spent 2 800 clocks per k-stage on 512 clocks of MFMA
+// work: LDS writes, their waits and un-overlapped fragment reads.)
+constexpr int R_BM = 128, R_BN = 128, R_NS = 4;
+constexpr int R_STAGE_BYTES = (R_BM + R_BN) * D_ROW;  // 32 KiB
+constexpr int R_LDS_BYTES = R_NS * R_STAGE_BYTES;     // 128 KiB
+
+template <int EPI>
+__global__ __launch_bounds__(512) void gemm_bf16_ring_kernel(const GemmArgs a, int tiles_m, int tiles_n,
+                                                             int mt_per_xcd, int n_bands) {
+  constexpr int FM = 2, FN = 1, TM = 64, TN = 32;
+  static_assert(8 * 32 * (TN * 4 + 16) <= R_LDS_BYTES, "epilogue staging must fit in the ring");
+  extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+
+  // ---- tile assignment: workgroup ids are dealt round-robin to the 8 XCDs; each XCD walks its own range of
+  //      row blocks in 8 x 4 tile groups so the tiles in flight on one XCD share A and W slices in its L2
+  const int xcd = blockIdx.x & 7, q = blockIdx.x >> 3;
+  const int blk = q / (GROUP_M * GROUP_N), r = q - blk * (GROUP_M * GROUP_N);
+  const int mb = blk / n_bands, nb = blk - mb * n_bands;
+  const int m_local = mb * GROUP_M + r / GROUP_N;
+  const int tile_m = xcd * mt_per_xcd + m_local, tile_n = nb * GROUP_N + (r % GROUP_N);
+  if (m_local >= mt_per_xcd || tile_m >= tiles_m || tile_n >= tiles_n) return;
+  const int m0 = tile_m * R_BM, n0 = tile_n * R_BN;
+
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int wm = wave >> 2, wn = wave & 3;
+  const int lrow = lane & 31, lk = lane >> 5;
+
+  // ---- loader: an instruction fills 8 rows of 128 bytes; wave w moves rows [16w, 16w + 16) of both
+  //      operand tiles.  The chunk that lands in LDS chunk c of row r is c ^ ((r >> 1) & 7).
+  const int ld_row = wave * 16 + (lane >> 3);
+  const int ld_chunk = (lane & 7) ^ (lane >> 4);
+  const uint32_t offA0 = (uint32_t)(ld_row * a.lda + ld_chunk * 8) * 2u;
+  const uint32_t offA1 = (uint32_t)((ld_row + 8) * a.lda + (ld_chunk ^ 4) * 8) * 2u;
+  const uint32_t offW0 = (uint32_t)(ld_row * a.ldw + ld_chunk * 8) * 2u;
+  const uint32_t offW1 = (uint32_t)((ld_row + 8) * a.ldw + (ld_chunk ^ 4) * 8) * 2u;
+  const unsigned char* const baseA = (const unsigned char*)a.A + (size_t)m0 * a.lda * 2;
+  const unsigned char* const baseW = (const unsigned char*)a.W + (size_t)n0 * a.ldw * 2;
+  auto dma16 = [&](const unsigned char* gbase, uint32_t goff, unsigned char* lptr) {
+    const uint32_t lds_addr = __builtin_amdgcn_readfirstlane((uint32_t)(uintptr_t)lptr);
+    asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, %2" ::"s"(lds_addr), "v"(goff), "s"(gbase)
+                 : "memory", "m0");
+  };
+  auto issue_stage = [&](int slot, int kt) {  // four instructions per wave
+    unsigned char* base = smem + slot * R_STAGE_BYTES + wave * 16 * D_ROW;
+    const unsigned char* ga = baseA + kt * D_ROW;
+    const unsigned char* gw = baseW + kt * D_ROW;
+    dma16(ga, offA0, base);
+    dma16(ga, offA1, base + 8 * D_ROW);
+    dma16(gw, offW0, base + R_BM * D_ROW);
+    dma16(gw, offW1, base + R_BM * D_ROW + 8 * D_ROW);
+  };
+
+  const int sw = (lrow >> 1) & 7;
+  const uint32_t fa_off = (uint32_t)((wm * TM + lrow) * D_ROW + ((lk ^ sw) << 4));
+  const uint32_t fb_off = (uint32_t)(R_BM * D_ROW + (wn * TN + lrow) * D_ROW + ((lk ^ sw) << 4));
+
+  f32x16 acc[FM][FN];
+#pragma unroll
+  for (int i = 0; i < FM; ++i)
+#pragma unroll
+    for (int v = 0; v < 16; ++v) acc[i][0][v] = 0.f;
+
+  const int KT = a.K / D_BK;
+  // The tail re-reads the last k-stage into slots nobody uses any more, so that every stage issues
+  // the same four loads and the wait below can count them.
+#pragma unroll
+  for (int s = 0; s < R_NS - 1; ++s) issue_stage(s, min(s, KT - 1));
+
+  bf16x8 fa[4][FM], fb[4];  // all four sub-steps of a stage are read up front: registers are plentiful here
+  for (int kt = 0; kt < KT; ++kt) {
+    const int slot = kt & (R_NS - 1);
+    // this wave's loads of stage kt have landed (those of the two later stages may be in flight) and
+    // its LDS reads of stage kt - 1 are complete; then meet the other waves
+    __builtin_amdgcn_s_waitcnt(0x0070 | (4 * (R_NS - 2)));
+    __builtin_amdgcn_s_barrier();
+    issue_stage((kt + R_NS - 1) & (R_NS - 1), min(kt + R_NS - 1, KT - 1));
+    const unsigned char* st = smem + slot * R_STAGE_BYTES;
+#pragma unroll
+    for (int ks = 0; ks < 4; ++ks) {
+#pragma unroll
+      for (int i = 0; i < FM; ++i) fa[ks][i] = *(const bf16x8*)(st + (fa_off ^ (uint32_t)(ks << 5)) + i * 32 * D_ROW);
+      fb[ks] = *(const bf16x8*)(st + (fb_off ^ (uint32_t)(ks << 5)));
+    }
+    __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+    for (int ks = 0; ks < 4; ++ks)
+#pragma unroll
+      for (int i = 0; i < FM; ++i)
+        acc[i][0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb[ks], fa[ks][i], acc[i][0], 0, 0, 0);
+    __builtin_amdgcn_sched_barrier(0);
+  }
+  // the trailing loads still write LDS, which the epilogue reuses
+  __builtin_amdgcn_s_waitcnt(0x0070);
+  __builtin_amdgcn_s_barrier();
+  wave_epilogue<EPI, FM, FN>(a, acc, smem, m0 + wm * TM, n0 + wn * TN, wave, lane);
+}
+
+hipError_t launch_ring(const GemmArgs& a, hipStream_t s) {
+  const int tiles_m = (a.M + R_BM - 1) / R_BM, tiles_n = (a.N + R_BN - 1) / R_BN;
+  const int mt_per_xcd = (tiles_m + 7) / 8;
+  const int n_bands = (tiles_n + GROUP_N - 1) / GROUP_N;
+  const int m_blocks = (mt_per_xcd + GROUP_M - 1) / GROUP_M;
+  const long grid = 8L * m_blocks * n_bands * GROUP_M * GROUP_N;
+  if (grid > 0x7fffffffL) return hipErrorInvalidValue;
+#define VIT_LAUNCH(EPI)                                                                                              \
+  do {                                                                                                               \
+    auto kfn = gemm_bf16_ring_kernel<EPI>;                                                                           \
+    static bool attr_set = false;                                                                                    \
+    if (!attr_set) {                                                                                                 \
+      hipError_t e = hipFuncSetAttribute((const void*)kfn, hipFuncAttributeMaxDynamicSharedMemorySize, R_LDS_BYTES); \
+      if (e != hipSuccess) return e;                                                                                 \
+      attr_set = true;                                                                                               \
+    }                                                                                                                \
+    hipLaunchKernelGGL(kfn, dim3((unsigned)grid), dim3(512), R_LDS_BYTES, s, a, tiles_m, tiles_n, mt_per_xcd,        \
+                       n_bands);                                                                                     \
+  } while (0)
+  switch (a.epilogue) {
+    case EPI_BIAS: VIT_LAUNCH(EPI_BIAS); break;
+    case EPI_BIAS_GELU: VIT_LAUNCH(EPI_BIAS_GELU); break;
+    case EPI_BIAS_RESIDUAL: VIT_LAUNCH(EPI_BIAS_RESIDUAL); break;
+    case EPI_PATCH: VIT_LAUNCH(EPI_PATCH); break;
+    default: return hipErrorInvalidValue;
+  }
+#undef VIT_LAUNCH
+  return hipGetLastError();
+}
+
 hipError_t launch_dma(const GemmArgs& a, hipStream_t s) {
   const int tiles_m = (a.M + D_BM - 1) / D_BM, tiles_n = (a.N + D_BN - 1) / D_BN;
   // column bands of four tiles; a remainder of one or two tile columns gets its own group shape
@@ -656,38 +690,6 @@ hipError_t launch_dma(const GemmArgs& a, hipStream_t s) {
   return hipGetLastError();
 }
 
-template <int BM, int BN, int WM, int WN>
-hipError_t launch_cfg(const GemmArgs& a, hipStream_t s) {
-  const int tiles_m = (a.M + BM - 1) / BM, tiles_n = (a.N + BN - 1) / BN;
-  const int mt_per_xcd = (tiles_m + 7) / 8;
-  const int n_bands = (tiles_n + GROUP_N - 1) / GROUP_N;
-  const int m_blocks = (mt_per_xcd + GROUP_M - 1) / GROUP_M;
-  const long grid = 8L * m_blocks * n_bands * GROUP_M * GROUP_N;
-  if (grid > 0x7fffffffL) return hipErrorInvalidValue;
-  const size_t smem = 2 * (BM + BN) * 128;
-  dim3 block(WM * WN * 64);
-#define VIT_LAUNCH(EPI)                                                                                              \
-  do {                                                                                                               \
-    auto kfn = gemm_bf16_kernel<BM, BN, WM, WN, EPI>;                                                                \
-    static bool attr_set = false; /* raising the dynamic LDS limit is needed once per kernel */                      \
-    if (!attr_set) {                                                                                                 \
-      hipError_t e = hipFuncSetAttribute((const void*)kfn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);   \
-      if (e != hipSuccess) return e;                                                                                 \
-      attr_set = true;                                                                                               \
-    }                                                                                                                \
-    hipLaunchKernelGGL(kfn, dim3((unsigned)grid), block, smem, s, a, tiles_m, tiles_n, mt_per_xcd, n_bands);         \
-  } while (0)
-  switch (a.epilogue) {
-    case EPI_BIAS: VIT_LAUNCH(EPI_BIAS); break;
-    case EPI_BIAS_GELU: VIT_LAUNCH(EPI_BIAS_GELU); break;
-    case EPI_BIAS_RESIDUAL: VIT_LAUNCH(EPI_BIAS_RESIDUAL); break;
-    case EPI_PATCH: VIT_LAUNCH(EPI_PATCH); break;
-    default: return hipErrorInvalidValue;
-  }
-#undef VIT_LAUNCH
-  return hipGetLastError();
-}
-
 }  // namespace
 
 int gemm_row_pad() { return 256; }
@@ -700,7 +702,7 @@ hipError_t launch_gemm_bf16(const GemmArgs& a, hipStream_t s) {
   // The persistent 256 x 256 kernel wants at least one tile per compute unit.
   const long big_tiles = (long)((a.M + 255) / 256) * ((a.N + 255) / 256);
   if (big_tiles >= 256) return launch_dma(a, s);
-  return launch_cfg<128, 128, 2, 2>(a, s);
+  return launch_ring(a, s);
 }
 
 }  // namespace vitenc
