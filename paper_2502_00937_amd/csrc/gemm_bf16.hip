@@ -5,8 +5,8 @@
 //
 // Two kernels share the fragment layout and the epilogues; both move their operands global -> LDS
 // directly (global_load_lds_dwordx4) and are described where they are defined:
-// * gemm_bf16_ring_kernel (below 256 tiles of 256 x 256): one 128 x 128 tile per workgroup, eight
-//   waves of 64 x 32, a ring of four 64-wide k-stages;
+// * gemm_bf16_ring_kernel (below 384 tiles of 256 x 256): one 128 x 128 tile per workgroup, eight
+//   waves of 64 x 32, a ring of four (or two) 64-wide k-stages;
 // * gemm_bf16_dma_kernel (everything large): persistent, 256 x 256 tiles, eight waves of 128 x 64,
 //   two 64-wide k-stages.
 // * LDS tiles are [row][64 bf16] with the 16-byte chunks XOR-swizzled by (row >> 1) & 7:
@@ -512,23 +512,26 @@ __global__ __launch_bounds__(512) void gemm_bf16_dma_kernel(const GemmArgs a, in
 }
 
 // ---------------------------------------------------------------------------------------------
-// Small-problem kernel (fewer than 256 tiles of 256 x 256): one 128 x 128 tile per workgroup, eight
-// waves of 64 x 32 (two per SIMD), operands global -> LDS directly into a ring of four 64-wide
-// k-stages (32 KiB each).  Here a workgroup is alone on its compute unit and nothing but its own
-// instruction order hides latency: the loads run three k-stages ahead, one wait + barrier per
-// stage establishes that the stage has landed for every wave and that the slot refilled next is
-// dead, and all fragments of a stage are read before its MFMAs start (registers are plentiful
-// here).  (The register-staged predecessor spent 2 800 clocks per k-stage on 512 clocks of MFMA
-// work: LDS writes, their waits and un-overlapped fragment reads.)
-constexpr int R_BM = 128, R_BN = 128, R_NS = 4;
+// Small-problem kernel (fewer than 384 tiles of 256 x 256): one 128 x 128 tile per workgroup, eight
+// waves of 64 x 32 (two per SIMD), operands global -> LDS directly into a ring of R_NS 64-wide
+// k-stages (32 KiB each).  One wait + barrier per stage establishes that the stage has landed for
+// every wave and that the slot refilled next is dead; all fragments of a stage are read before
+// its MFMAs start (registers are plentiful here).
+// * R_NS = 4 when there are no more tiles than compute units: a workgroup is then alone on its
+//   unit and nothing but its own instruction order hides latency, so the loads run three stages
+//   ahead.
+// * R_NS = 2 (64 KiB) otherwise: two workgroups share a unit and cover each other's waits, and a
+//   grid of 1.2 or 1.7 rounds no longer costs 2.
+// (The register-staged predecessor spent 2 800 clocks per k-stage on 512 clocks of MFMA work: LDS
+// writes, their waits and un-overlapped fragment reads.)
+constexpr int R_BM = 128, R_BN = 128;
 constexpr int R_STAGE_BYTES = (R_BM + R_BN) * D_ROW;  // 32 KiB
-constexpr int R_LDS_BYTES = R_NS * R_STAGE_BYTES;     // 128 KiB
 
-template <int EPI>
+template <int EPI, int R_NS>
 __global__ __launch_bounds__(512) void gemm_bf16_ring_kernel(const GemmArgs a, int tiles_m, int tiles_n,
                                                              int mt_per_xcd, int n_bands) {
   constexpr int FM = 2, FN = 1, TM = 64, TN = 32;
-  static_assert(8 * 32 * (TN * 4 + 16) <= R_LDS_BYTES, "epilogue staging must fit in the ring");
+  static_assert(8 * 32 * (TN * 4 + 16) <= R_NS * R_STAGE_BYTES, "epilogue staging must fit in the ring");
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
 
   // ---- tile assignment: workgroup ids are dealt round-robin to the 8 XCDs; each XCD walks its own range of
@@ -623,17 +626,27 @@ hipError_t launch_ring(const GemmArgs& a, hipStream_t s) {
   const int m_blocks = (mt_per_xcd + GROUP_M - 1) / GROUP_M;
   const long grid = 8L * m_blocks * n_bands * GROUP_M * GROUP_N;
   if (grid > 0x7fffffffL) return hipErrorInvalidValue;
-#define VIT_LAUNCH(EPI)                                                                                              \
+  // More tiles than compute units: two-stage rings (64 KiB) so that two workgroups share a unit and
+  // the rounds overlap; otherwise the four-stage ring, whose loads run three stages ahead.
+  const bool two = (long)tiles_m * tiles_n > 256;
+#define VIT_LAUNCH_NS(EPI, NS)                                                                                       \
   do {                                                                                                               \
-    auto kfn = gemm_bf16_ring_kernel<EPI>;                                                                           \
+    auto kfn = gemm_bf16_ring_kernel<EPI, NS>;                                                                       \
+    constexpr int lds = NS * R_STAGE_BYTES;                                                                          \
     static bool attr_set = false;                                                                                    \
     if (!attr_set) {                                                                                                 \
-      hipError_t e = hipFuncSetAttribute((const void*)kfn, hipFuncAttributeMaxDynamicSharedMemorySize, R_LDS_BYTES); \
+      hipError_t e = hipFuncSetAttribute((const void*)kfn, hipFuncAttributeMaxDynamicSharedMemorySize, lds);         \
       if (e != hipSuccess) return e;                                                                                 \
       attr_set = true;                                                                                               \
     }                                                                                                                \
-    hipLaunchKernelGGL(kfn, dim3((unsigned)grid), dim3(512), R_LDS_BYTES, s, a, tiles_m, tiles_n, mt_per_xcd,        \
-                       n_bands);                                                                                     \
+    hipLaunchKernelGGL(kfn, dim3((unsigned)grid), dim3(512), lds, s, a, tiles_m, tiles_n, mt_per_xcd, n_bands);      \
+  } while (0)
+#define VIT_LAUNCH(EPI)           \
+  do {                            \
+    if (two)                      \
+      VIT_LAUNCH_NS(EPI, 2);      \
+    else                          \
+      VIT_LAUNCH_NS(EPI, 4);      \
   } while (0)
   switch (a.epilogue) {
     case EPI_BIAS: VIT_LAUNCH(EPI_BIAS); break;
@@ -643,6 +656,7 @@ hipError_t launch_ring(const GemmArgs& a, hipStream_t s) {
     default: return hipErrorInvalidValue;
   }
 #undef VIT_LAUNCH
+#undef VIT_LAUNCH_NS
   return hipGetLastError();
 }
 
@@ -699,9 +713,11 @@ hipError_t launch_gemm_bf16(const GemmArgs& a, hipStream_t s) {
   // 16-byte epilogue accesses need 8-element aligned columns and leading dimensions
   if (a.K <= 0 || a.K % BK != 0 || a.lda % 8 != 0 || a.ldw % 8 != 0 || a.ldo % 8 != 0 || a.N % 8 != 0)
     return hipErrorInvalidValue;
-  // The persistent 256 x 256 kernel wants at least one tile per compute unit.
+  // The persistent 256 x 256 kernel pays off from about one and a half tiles per compute unit
+  // (measured crossover between 300 and 440 tiles on the encoder's shapes); below that its last,
+  // partly filled round costs more than the smaller tiles' extra operand traffic.
   const long big_tiles = (long)((a.M + 255) / 256) * ((a.N + 255) / 256);
-  if (big_tiles >= 256) return launch_dma(a, s);
+  if (big_tiles >= 384) return launch_dma(a, s);
   return launch_ring(a, s);
 }
 
