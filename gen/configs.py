@@ -13,12 +13,12 @@ from __future__ import annotations
 _KEYS = (
     "image_size", "patch_size", "channels", "hidden", "heads", "mlp",
     "layers_local", "layers_global", "has_cls", "final_ln", "ln_eps",
-    "proj_layers", "proj_dims", "dtype",
+    "proj_layers", "proj_dims", "dtype", "token_merge",
 )
 
 
 def _cfg(image_size, patch_size, hidden, heads, mlp, layers_local, layers_global=0,
-         has_cls=1, final_ln=1, ln_eps=1e-6, proj_dims=(), dtype="bf16", channels=3):
+         has_cls=1, final_ln=1, ln_eps=1e-6, proj_dims=(), dtype="bf16", channels=3, token_merge=1):
     proj_dims = tuple(int(d) for d in proj_dims)
     assert len(proj_dims) <= 2
     return {
@@ -27,6 +27,7 @@ def _cfg(image_size, patch_size, hidden, heads, mlp, layers_local, layers_global
         "layers_local": layers_local, "layers_global": layers_global,
         "has_cls": has_cls, "final_ln": final_ln, "ln_eps": ln_eps,
         "proj_layers": len(proj_dims), "proj_dims": proj_dims, "dtype": dtype,
+        "token_merge": token_merge,
     }
 
 
@@ -40,6 +41,11 @@ CONFIGS = {
     # 5: ViT-H/14 at 560 px tiles -> 1600 + CLS = 1601 tokens per tile (Table 1),
     #    32 tile-local layers then 8 layers attending over all tiles of an image
     "cfg5_vith14_560": _cfg(560, 14, 1280, 16, 5120, 32, layers_global=8),
+    # 6 (second workload): a 6 B-class encoder on 448-px tiles whose 32 x 32 patch tokens are down-sampled
+    #    2 x 2 to the 256 tokens per tile of Table 1 (5 x 256 = 1280 per image).  The paper names the size
+    #    class only; width, depth and the projector widths are this repository's choice for that class
+    #    (45 blocks of hidden 3200 = 25 heads of 128, MLP 12800: 5.5 G parameters; projector 12800 -> 6144 -> 6144).
+    "cfg6_6b_448": _cfg(448, 14, 3200, 25, 12800, 45, proj_dims=(6144, 6144), token_merge=2),
     # ---- small test shapes (not benchmark workloads) ----
     # head dim 64, CLS, local+global, 2-layer projector, odd patch count
     "test_small_bf16": _cfg(56, 14, 128, 2, 256, 2, layers_global=1, proj_dims=(192, 160)),
@@ -56,6 +62,11 @@ CONFIGS = {
     "test_medium_fp32": _cfg(210, 14, 256, 4, 512, 2, layers_global=1, proj_dims=(256, 128), dtype="fp32"),
     # odd numbers of 64-wide k-stages (1, 3, 5) and one, two and three tile columns: 14x14 + 1 = 197 tokens
     "test_oddk_bf16": _cfg(56, 4, 192, 3, 320, 2),
+    # token down-sampling: 8 x 8 patches + CLS = 65 tokens per tile -> 4 x 4 = 16 output tokens of 4 * 128
+    # channels, 2-layer projector; without CLS, no projector and 3 x 3 blocks (g = 6 -> 2 x 2 = 4 tokens of 9 * 64)
+    "test_merge_bf16": _cfg(56, 7, 128, 2, 256, 1, layers_global=1, proj_dims=(192, 160), token_merge=2),
+    "test_merge_fp32": _cfg(56, 7, 128, 2, 256, 1, layers_global=1, proj_dims=(192, 160), token_merge=2, dtype="fp32"),
+    "test_merge3_bf16": _cfg(60, 10, 64, 1, 128, 2, has_cls=0, final_ln=0, token_merge=3),
 }
 
 
@@ -69,6 +80,17 @@ def tokens_per_tile(cfg: dict) -> int:
     """Tokens one tile yields: floor(S/p)^2 patches plus one CLS row if present (Table 1)."""
     g = cfg["image_size"] // cfg["patch_size"]
     return g * g + (1 if cfg["has_cls"] else 0)
+
+
+def out_tokens_per_tile(cfg: dict) -> int:
+    """Tokens one tile hands on: all of them, or (g / m)^2 after m x m token down-sampling
+    (Table 1: 448-px tiles -> 256 tokens)."""
+    m = cfg["token_merge"]
+    if m <= 1:
+        return tokens_per_tile(cfg)
+    g = cfg["image_size"] // cfg["patch_size"]
+    assert g % m == 0
+    return (g // m) ** 2
 
 
 def weight_layout(cfg: dict):
@@ -96,7 +118,7 @@ def weight_layout(cfg: dict):
         ]
     if cfg["final_ln"]:
         out += [("lnf_g", (D,)), ("lnf_b", (D,))]
-    d_in = D
+    d_in = D * max(cfg["token_merge"], 1) ** 2
     for i in range(cfg["proj_layers"]):
         d_out = cfg["proj_dims"][i]
         out += [(f"proj{i}_w", (d_out, d_in)), (f"proj{i}_b", (d_out,))]

@@ -24,7 +24,12 @@ Readings taken where the paper is silent (it gives no ViT equations):
   * local layer: keys = the tile's own tokens; global layer: keys = all tokens of
     all tiles of the same image in tile order (Table 1: 4 x 1601 = 6404);
   * final LN (optional) then 0/1/2-layer projector with GELU between layers, applied
-    to every token; all tokens are output in input tile order.
+    to every token; all tokens are output in input tile order;
+  * token down-sampling (Table 1 lists 448-px tiles with 256 tokens each, a quarter of the
+    32 x 32 patch grid; the paper does not say how): after the final LN the CLS row is
+    dropped and every m x m block of neighbouring patch tokens becomes one token whose
+    channels are the block's tokens one after the other, rows of the block first; the
+    projector then takes m*m*D inputs.
 
 Pins (tests/test_oracle_*.py): Table 1 token counts; patch matmul == brute-force
 strided convolution; softmax/LN/GELU closed forms; zero-block identity; single-tile
@@ -74,7 +79,7 @@ def unpack_weights(cfg: dict, flat: np.ndarray, dtype=np.float64) -> dict:
     if cfg["final_ln"]:
         w["lnf_g"], w["lnf_b"] = take(D), take(D)
     w["proj"] = []
-    d_in = D
+    d_in = D * max(cfg.get("token_merge", 1), 1) ** 2
     for i in range(cfg["proj_layers"]):
         d_out = cfg["proj_dims"][i]
         w["proj"].append((take(d_out, d_in), take(d_out)))
@@ -89,6 +94,38 @@ def tokens_per_tile(cfg: dict) -> int:
     """g^2 patches (+1 CLS); g = floor(S/p).  Table 1: 560/14 -> 1600+1, 384/14 -> 27^2 = 729."""
     g = cfg["image_size"] // cfg["patch_size"]
     return g * g + (1 if cfg["has_cls"] else 0)
+
+
+def out_tokens_per_tile(cfg: dict) -> int:
+    """Tokens a tile hands on: all T, or (g/m)^2 after m x m down-sampling.  Table 1: 448/14 = 32,
+    m = 2 -> 16^2 = 256 tokens per tile, 5 tiles -> 1280 per image."""
+    m = cfg.get("token_merge", 1)
+    if m <= 1:
+        return tokens_per_tile(cfg)
+    g = cfg["image_size"] // cfg["patch_size"]
+    if g % m:
+        raise ValueError("the patch grid must be a multiple of token_merge")
+    return (g // m) ** 2
+
+
+def merge_tokens(x: np.ndarray, cfg: dict) -> np.ndarray:
+    """Token down-sampling of ONE tile: x [T, D] -> [(g/m)^2, m*m*D].
+
+    Output token (Y, X) is the concatenation of patch tokens (m*Y + dy, m*X + dx) for dy = 0..m-1
+    (outer), dx = 0..m-1 (inner); patch (y, x) is row cls + y*g + x of x.  The CLS row is dropped."""
+    m = cfg["token_merge"]
+    g = cfg["image_size"] // cfg["patch_size"]
+    cls = 1 if cfg["has_cls"] else 0
+    D = x.shape[1]
+    gm = g // m
+    out = np.empty((gm * gm, m * m * D), dtype=x.dtype)
+    for Y in range(gm):
+        for X in range(gm):
+            for dy in range(m):
+                for dx in range(m):
+                    q = dy * m + dx
+                    out[Y * gm + X, q * D:(q + 1) * D] = x[cls + (m * Y + dy) * g + (m * X + dx)]
+    return out
 
 
 def linear(x: np.ndarray, w: np.ndarray, b: np.ndarray) -> np.ndarray:
@@ -164,7 +201,7 @@ def block(x: np.ndarray, lw: dict, cfg: dict, segments) -> np.ndarray:
 
 
 def encode_image(tiles: np.ndarray, w: dict, cfg: dict) -> np.ndarray:
-    """All tiles of ONE image [n, C, S, S] -> [n*T, out_dim]."""
+    """All tiles of ONE image [n, C, S, S] -> [n*T_out, out_dim]."""
     n = tiles.shape[0]
     T = tokens_per_tile(cfg)
     x = np.concatenate([patch_embed(tiles[i], w, cfg) for i in range(n)], axis=0)
@@ -174,6 +211,8 @@ def encode_image(tiles: np.ndarray, w: dict, cfg: dict) -> np.ndarray:
         x = block(x, lw, cfg, local if l < cfg["layers_local"] else whole)
     if cfg["final_ln"]:
         x = layer_norm(x, w["lnf_g"], w["lnf_b"], cfg["ln_eps"])
+    if cfg.get("token_merge", 1) > 1:
+        x = np.concatenate([merge_tokens(x[i * T:(i + 1) * T], cfg) for i in range(n)], axis=0)
     for i, (pw, pb) in enumerate(w["proj"]):
         if i > 0:
             x = gelu(x)
@@ -184,7 +223,7 @@ def encode_image(tiles: np.ndarray, w: dict, cfg: dict) -> np.ndarray:
 # --------------------------------------------------------------------------- packed entry point
 def request_token_offsets(cfg: dict, images_per_request, tile_offsets) -> np.ndarray:
     """Prefix sums: first output token row of each request (length n_requests + 1)."""
-    T = tokens_per_tile(cfg)
+    T = out_tokens_per_tile(cfg)
     ipr = np.asarray(images_per_request, dtype=np.int64)
     to = np.asarray(tile_offsets, dtype=np.int64)
     img_end = np.concatenate([[0], np.cumsum(ipr)])
@@ -193,7 +232,7 @@ def request_token_offsets(cfg: dict, images_per_request, tile_offsets) -> np.nda
 
 def vit_oracle_encode(cfg: dict, weights, pixels: np.ndarray, images_per_request, tile_offsets,
                       dtype=np.float64, images=None):
-    """Encode a packed batch.  Returns (tokens [n_tiles*T, out_dim], request_token_offsets).
+    """Encode a packed batch.  Returns (tokens [n_tiles*T_out, out_dim], request_token_offsets).
 
     `weights` is the flat buffer or an already unpacked dict.  `images`, if given, lists
     the image indices to encode; rows of other images are left as NaN (each image's
@@ -209,8 +248,9 @@ def vit_oracle_encode(cfg: dict, weights, pixels: np.ndarray, images_per_request
     if pixels.shape[0] != to[-1]:
         raise ValueError("pixels hold a different number of tiles than tile_offsets")
     w = weights if isinstance(weights, dict) else unpack_weights(cfg, weights, dtype)
-    T = tokens_per_tile(cfg)
-    out_dim = cfg["proj_dims"][cfg["proj_layers"] - 1] if cfg["proj_layers"] else cfg["hidden"]
+    T = out_tokens_per_tile(cfg)
+    out_dim = (cfg["proj_dims"][cfg["proj_layers"] - 1] if cfg["proj_layers"]
+               else cfg["hidden"] * max(cfg.get("token_merge", 1), 1) ** 2)
     out = np.full((int(to[-1]) * T, out_dim), np.nan, dtype=dtype)
     for i in (range(n_images) if images is None else images):
         a, b = int(to[i]), int(to[i + 1])

@@ -21,12 +21,14 @@ def tiny_cfg(**kw):
 def test_table1_token_counts():
     rows = [l.split() for l in open(os.path.join(HERE, "golden", "table1_token_counts.txt"))
             if l.strip() and not l.startswith("#")]
-    assert len(rows) == 2
-    for S, p, cls, T, n, total in (map(int, r) for r in rows):
-        cfg = tiny_cfg(image_size=S, patch_size=p, has_cls=cls)
-        assert O.tokens_per_tile(cfg) == T
-        assert n * O.tokens_per_tile(cfg) == total
-        assert gen.tokens_per_tile(cfg) == T
+    assert len(rows) == 3
+    for S, p, cls, m, T, n, total in (map(int, r) for r in rows):
+        cfg = tiny_cfg(image_size=S, patch_size=p, has_cls=cls, token_merge=m)
+        assert O.out_tokens_per_tile(cfg) == T
+        assert n * O.out_tokens_per_tile(cfg) == total
+        assert gen.out_tokens_per_tile(cfg) == T
+        if m == 1:
+            assert O.tokens_per_tile(cfg) == T and gen.tokens_per_tile(cfg) == T
 
 
 def test_config_shapes():
@@ -34,6 +36,57 @@ def test_config_shapes():
     assert O.tokens_per_tile(gen.get_config("cfg2_vitl14_336")) == 577
     assert O.tokens_per_tile(gen.get_config("cfg4_siglip_384")) == 729
     assert O.tokens_per_tile(gen.get_config("cfg5_vith14_560")) == 1601
+    cfg6 = gen.get_config("cfg6_6b_448")
+    assert O.tokens_per_tile(cfg6) == 1025 and O.out_tokens_per_tile(cfg6) == 256
+
+
+# ------------------------------------------------------------------ token down-sampling
+def test_token_merge_by_hand():
+    """2 x 2 grid, D = 2, CLS: the four patch tokens end up side by side in (row, column) order."""
+    cfg = tiny_cfg(image_size=4, patch_size=2, has_cls=1, token_merge=2)
+    x = np.array([[9., 9.], [1., 2.], [3., 4.], [5., 6.], [7., 8.]])
+    np.testing.assert_array_equal(O.merge_tokens(x, cfg), [[1., 2., 3., 4., 5., 6., 7., 8.]])
+    # 4 x 4 grid, D = 1, no CLS, value = 10*y + x: token (Y, X) holds its block row by row
+    cfg = tiny_cfg(image_size=8, patch_size=2, has_cls=0, token_merge=2)
+    x = np.array([[10. * y + xx] for y in range(4) for xx in range(4)])
+    np.testing.assert_array_equal(O.merge_tokens(x, cfg),
+                                  [[0, 1, 10, 11], [2, 3, 12, 13], [20, 21, 30, 31], [22, 23, 32, 33]])
+
+
+@pytest.mark.parametrize("g,m,cls,D", [(4, 2, 1, 3), (6, 3, 0, 2), (6, 2, 1, 5), (8, 4, 0, 1)])
+def test_token_merge_is_a_reshape_transpose_and_a_permutation(g, m, cls, D):
+    cfg = tiny_cfg(image_size=g * 2, patch_size=2, has_cls=cls, token_merge=m)
+    x = np.arange((g * g + cls) * D, dtype=np.float64).reshape(g * g + cls, D) + 1.0
+    got = O.merge_tokens(x, cfg)
+    gm = g // m
+    # the same re-layout as one reshape / transpose of the patch grid
+    want = x[cls:].reshape(gm, m, gm, m, D).transpose(0, 2, 1, 3, 4).reshape(gm * gm, m * m * D)
+    np.testing.assert_array_equal(got, want)
+    # every patch value exactly once, the CLS values (if any) not at all
+    assert sorted(got.ravel().tolist()) == sorted(x[cls:].ravel().tolist())
+    assert O.out_tokens_per_tile(cfg) == gm * gm
+
+
+def test_token_merge_sits_between_final_ln_and_projector():
+    """Encoder with down-sampling == down-sampling applied by hand to the encoder without it (no
+    projector), and == projector applied by hand to that (1-layer projector)."""
+    base = gen.get_config("test_merge_fp32")
+    base.update(proj_layers=0, proj_dims=())
+    plain = dict(base, token_merge=1)
+    flat = gen.make_weights(plain, seed=3)
+    px = gen.make_pixels(plain, 3, seed=4)
+    T = O.tokens_per_tile(plain)
+    full, _ = O.vit_oracle_encode(plain, flat, px, [2], [0, 1, 3])
+    merged, rto = O.vit_oracle_encode(base, flat, px, [2], [0, 1, 3])
+    want = np.concatenate([O.merge_tokens(full[t * T:(t + 1) * T], base) for t in range(3)])
+    np.testing.assert_array_equal(merged, want)
+    assert rto.tolist() == [0, 3 * O.out_tokens_per_tile(base)]
+    withp = dict(base, proj_layers=1, proj_dims=(24,))
+    rng = np.random.default_rng(5)
+    pw, pb = rng.standard_normal((24, 4 * base["hidden"])), rng.standard_normal(24)
+    flat_p = np.concatenate([flat, pw.ravel(), pb]).astype(np.float64)
+    got, _ = O.vit_oracle_encode(withp, flat_p, px, [2], [0, 1, 3])
+    np.testing.assert_allclose(got, want @ pw.T + pb, rtol=1e-12, atol=1e-12)
 
 
 # ------------------------------------------------------------------ patchify

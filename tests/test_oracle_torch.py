@@ -13,7 +13,7 @@ from oracle import vit_oracle as O
 
 
 def torch_encode_image(cfg, flat, tiles):
-    """tiles [n, C, S, S] of one image -> [n*T, out_dim] float64."""
+    """tiles [n, C, S, S] of one image -> [n*T_out, out_dim] float64."""
     f = torch.from_numpy(np.asarray(flat, dtype=np.float64))
     pos = 0
 
@@ -56,6 +56,14 @@ def torch_encode_image(cfg, flat, tiles):
     if cfg["final_ln"]:
         x = F.layer_norm(x, (D,), take(D), take(D), cfg["ln_eps"])
     d_in = D
+    m = cfg["token_merge"]
+    if m > 1:
+        # library routine: pixel_unshuffle turns [*, D, g, g] into [*, D*m*m, g/m, g/m] with channel
+        # index c*m*m + dy*m + dx; the encoder's channel order is (dy, dx, c), hence the permute
+        x = x.reshape(n, T, D)[:, cfg["has_cls"]:, :].transpose(1, 2).reshape(n, D, g, g)
+        x = F.pixel_unshuffle(x, m)                           # [n, D*m*m, g/m, g/m]
+        x = x.reshape(n, D, m * m, (g // m) ** 2).permute(0, 3, 2, 1).reshape(n * (g // m) ** 2, m * m * D)
+        d_in = m * m * D
     for i in range(cfg["proj_layers"]):
         d_out = cfg["proj_dims"][i]
         if i > 0:
@@ -74,6 +82,8 @@ CASES = [
     ("cfg1_tiny_fp32", [1, 1]),
     ("test_dh96_bf16", [2, 1]),
     ("test_dh128_bf16", [1, 2]),
+    ("test_merge_fp32", [2, 1]),
+    ("test_merge3_bf16", [1, 2]),
 ]
 
 
@@ -86,7 +96,7 @@ def test_oracle_matches_torch_functional(name, tpi):
     to = np.concatenate([[0], np.cumsum(tpi)]).astype(np.int32)
     px = gen.make_pixels(cfg, int(to[-1]), seed=1)
     out, _ = O.vit_oracle_encode(cfg, flat, px, [len(tpi)], to)
-    T = O.tokens_per_tile(cfg)
+    T = O.out_tokens_per_tile(cfg)
     for i in range(len(tpi)):
         want = torch_encode_image(cfg, flat, px[to[i]:to[i + 1]])
         got = out[to[i] * T:to[i + 1] * T]
