@@ -37,7 +37,9 @@ enum { VIT_DTYPE_FP32 = 0, VIT_DTYPE_BF16 = 1 };
 
 /*
  * Encoder shape.  Tokens per tile T = floor(image_size/patch_size)^2 + has_cls
- * (paper Table 1: 560/14 with CLS -> 1601; 384/14 without -> 729).
+ * (paper Table 1: 560/14 with CLS -> 1601; 384/14 without -> 729).  Output tokens per tile
+ * T_out = T, or (floor(image_size/patch_size) / token_merge)^2 with token down-sampling
+ * (Table 1: 448/14 = 32, merged 2 x 2 -> 256).
  */
 typedef struct {
   int32_t image_size;    /* S: tiles are S x S pixels                                           */
@@ -56,6 +58,12 @@ typedef struct {
   int32_t dtype;         /* VIT_DTYPE_FP32: fp32 arithmetic and output;                         */
                          /* VIT_DTYPE_BF16: bf16 matrix operands, fp32 accumulation and         */
                          /* residual stream, bf16 output                                        */
+  int32_t token_merge;   /* 0 or 1: every token is output.  m > 1: token down-sampling after    */
+                         /* the final LayerNorm (paper Table 1: 448-px tiles -> 256 tokens): the */
+                         /* CLS row is dropped and every m x m block of neighbouring patch       */
+                         /* tokens becomes one token of m*m*D channels, the block's tokens one   */
+                         /* after the other in (row, column) order; floor(S/p) must be a         */
+                         /* multiple of m.  The projector (if any) then takes m*m*D inputs.      */
 } vit_config_t;
 
 /*
@@ -66,7 +74,8 @@ typedef struct {
  *   per block: ln1_g, ln1_b [D]; wqkv [3D, D] (rows: all of Q, then K, then V; head h is
  *   rows h*dh..), bqkv [3D]; wo [D, D], bo [D]; ln2_g, ln2_b [D]; w1 [M, D], b1 [M];
  *   w2 [D, M], b2 [D];
- *   lnf_g, lnf_b [D] (if final_ln); per projector layer: w [out, in], b [out].
+ *   lnf_g, lnf_b [D] (if final_ln); per projector layer: w [out, in], b [out]; the first
+ *   projector layer has in = D, or token_merge^2 * D with token down-sampling.
  */
 size_t vit_weight_count(const vit_config_t* cfg);
 
@@ -84,7 +93,8 @@ vit_status_t vit_encoder_create(const vit_config_t* cfg, const float* weights, s
 
 /*
  * Pure host function: what a launch over n_tiles tiles grouped into n_images images
- * produces and needs.  n_tokens = n_tiles * T; out_dim = last projector width, or D;
+ * produces and needs.  n_tokens = n_tiles * T_out; out_dim = last projector width, or D
+ * (token_merge^2 * D with token down-sampling and no projector);
  * workspace_bytes is an upper bound valid for any grouping of n_tiles tiles into
  * n_images >= 1 images.  Any output pointer may be NULL.
  */
@@ -100,7 +110,7 @@ vit_status_t vit_encoder_query(const vit_encoder_t* enc, int32_t n_tiles, int32_
  *                       an empty token range); sum = n_images.
  *   tile_offsets        HOST, [n_images + 1], prefix sum of tiles per image:
  *                       [0] = 0, strictly increasing, last = n_tiles.
- *   out_tokens          DEVICE, [n_tiles * T, out_dim] row-major, bf16 or fp32 per dtype,
+ *   out_tokens          DEVICE, [n_tiles * T_out, out_dim] row-major, bf16 or fp32 per dtype,
  *                       in input tile order; out_capacity_bytes is its size.
  *   request_token_offsets  HOST, optional [n_requests + 1]: first token row of each request.
  *   workspace           DEVICE scratch of at least vit_encoder_query's workspace_bytes,
@@ -136,7 +146,7 @@ const char* vit_last_error(void);
  * kernel launches per family.
  */
 enum {
-  VIT_PROF_PATCHIFY = 0, /* patch gather + CLS rows                 */
+  VIT_PROF_PATCHIFY = 0, /* patch gather, CLS rows, token down-sampling */
   VIT_PROF_GEMM = 1,     /* all matrix products incl. patch GEMM    */
   VIT_PROF_LAYERNORM = 2,
   VIT_PROF_ATTENTION = 3,

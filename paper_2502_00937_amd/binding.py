@@ -27,6 +27,7 @@ class vit_config_t(C.Structure):
         ("layers_local", C.c_int32), ("layers_global", C.c_int32),
         ("has_cls", C.c_int32), ("final_ln", C.c_int32), ("ln_eps", C.c_float),
         ("proj_layers", C.c_int32), ("proj_dims", C.c_int32 * 2), ("dtype", C.c_int32),
+        ("token_merge", C.c_int32),
     ]
 
 
@@ -94,6 +95,7 @@ def _to_struct(cfg: dict) -> vit_config_t:
     dims = list(cfg["proj_dims"]) + [0, 0]
     c.proj_dims[0], c.proj_dims[1] = int(dims[0]), int(dims[1])
     c.dtype = {"fp32": VIT_DTYPE_FP32, "bf16": VIT_DTYPE_BF16}[cfg["dtype"]]
+    c.token_merge = int(cfg.get("token_merge", 1))
     return c
 
 

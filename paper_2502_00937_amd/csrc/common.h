@@ -155,6 +155,10 @@ hipError_t launch_patch_gather(const float* pixels, void* patches, int ld, int n
 hipError_t launch_cls_rows(float* x, int ldx, const float* cls, const float* pos, int n_tiles, int T, int D,
                            hipStream_t s);
 hipError_t launch_fill_zero_cols(void* buf, int ld, int rows, int col0, int col1, int elem_bytes, hipStream_t s);
+// dst[tile*(g/m)^2 + y2*(g/m) + x2, (dy*m + dx)*D + c] = src[tile*T + cls + (y2*m + dy)*g + x2*m + dx, c];
+// columns [m*m*D, dst_ld) of dst are zeroed
+hipError_t launch_token_merge(const void* src, int src_ld, void* dst, int dst_ld, int n_tiles, int T, int cls, int g,
+                              int m, int D, int elem_bytes, hipStream_t s);
 
 int attention_q_block(int dtype_bf16, int dh_pad);  // query rows per work item for each path and head dim
 int gemm_row_pad();                     // row padding every activation buffer must have

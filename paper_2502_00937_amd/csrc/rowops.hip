@@ -119,6 +119,30 @@ __global__ __launch_bounds__(256) void fill_zero_cols_kernel(T* buf, int ld, lon
   buf[(idx / ncols) * ld + col0 + (int)(idx % ncols)] = (T)0;
 }
 
+// Token down-sampling: every m x m block of neighbouring patch tokens of a tile becomes one token whose
+// channels are the block's tokens one after the other, (dy, dx) row-major; the CLS row is dropped.
+// One thread moves 16 bytes; src rows are [tile*T + cls + y*g + x], dst rows [tile*(g/m)^2 + y2*(g/m) + x2].
+__global__ __launch_bounds__(256) void token_merge_kernel(const unsigned char* __restrict__ src, long src_ld_bytes,
+                                                          unsigned char* __restrict__ dst, long dst_ld_bytes,
+                                                          long n_out, int T, int cls, int g, int m, int row_chunks,
+                                                          int pad_chunks) {
+  const int chunks = m * m * row_chunks + pad_chunks;  // 16-byte chunks per output row, padding included
+  const long idx = (long)blockIdx.x * 256 + threadIdx.x;
+  if (idx >= n_out * chunks) return;
+  const long r = idx / chunks;
+  const int c = (int)(idx - r * chunks);
+  u32x4 v = {0u, 0u, 0u, 0u};
+  if (c < m * m * row_chunks) {
+    const int gm = g / m, pm = gm * gm;
+    const long tile = r / pm;
+    const int o = (int)(r - tile * pm), y2 = o / gm, x2 = o - y2 * gm;
+    const int q = c / row_chunks, k = c - q * row_chunks, dy = q / m, dx = q - dy * m;
+    const long srow = tile * T + cls + (long)(y2 * m + dy) * g + (x2 * m + dx);
+    v = *(const u32x4*)(src + srow * src_ld_bytes + (long)k * 16);
+  }
+  *(u32x4*)(dst + r * dst_ld_bytes + (long)c * 16) = v;
+}
+
 template <typename OutT, int NORMALIZE>
 hipError_t ln_dispatch(const float* x, int ldx, void* out, int ldo, int out_cols, const float* gamma, const float* beta,
                        float eps, int rows, int D, int reverse, hipStream_t s) {
@@ -174,6 +198,25 @@ hipError_t launch_cls_rows(float* x, int ldx, const float* cls, const float* pos
   if (total <= 0) return hipSuccess;
   hipLaunchKernelGGL(cls_rows_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, s, x, ldx, cls, pos, n_tiles,
                      T, D);
+  return hipGetLastError();
+}
+
+hipError_t launch_token_merge(const void* src, int src_ld, void* dst, int dst_ld, int n_tiles, int T, int cls, int g,
+                              int m, int D, int elem_bytes, hipStream_t s) {
+  const long n_out = (long)n_tiles * (g / m) * (g / m);
+  if (n_out <= 0) return hipSuccess;
+  // 16-byte moves: the channel count and both leading dimensions must be whole chunks
+  if (m < 1 || g % m != 0 || ((long)D * elem_bytes) % 16 != 0 || ((long)src_ld * elem_bytes) % 16 != 0 ||
+      ((long)dst_ld * elem_bytes) % 16 != 0 || dst_ld < m * m * D)
+    return hipErrorInvalidValue;
+  const int row_chunks = D * elem_bytes / 16;
+  const int pad_chunks = (dst_ld - m * m * D) * elem_bytes / 16;
+  const long total = n_out * (m * m * row_chunks + pad_chunks);
+  const long blocks = (total + 255) / 256;
+  if (blocks > 0x7fffffffL) return hipErrorInvalidValue;
+  hipLaunchKernelGGL(token_merge_kernel, dim3((unsigned)blocks), dim3(256), 0, s, (const unsigned char*)src,
+                     (long)src_ld * elem_bytes, (unsigned char*)dst, (long)dst_ld * elem_bytes, n_out, T, cls, g, m,
+                     row_chunks, pad_chunks);
   return hipGetLastError();
 }
 

@@ -62,6 +62,9 @@ struct Dims {
   int es;    // bytes per activation element
   float eps;
   int has_cls, final_ln;
+  int merge;     // token down-sampling factor (1 = none)
+  int T_out;     // output tokens per tile
+  int pin, pin_ld;  // inputs of the first projector layer (merge^2 * D) and its padded leading dimension
 };
 
 bool derive(const vit_config_t* c, Dims* d, const char** why) {
@@ -84,6 +87,11 @@ bool derive(const vit_config_t* c, Dims* d, const char** why) {
     if (c->proj_dims[i] <= 0 || c->proj_dims[i] % 8 != 0) { *why = "proj_dims must be positive multiples of 8"; return false; }
   if (c->dtype != VIT_DTYPE_FP32 && c->dtype != VIT_DTYPE_BF16) { *why = "dtype must be VIT_DTYPE_FP32 or VIT_DTYPE_BF16"; return false; }
   if (c->hidden > 4096) { *why = "hidden must be <= 4096"; return false; }
+  if (c->token_merge < 0 || c->token_merge > 8) { *why = "token_merge must be in [0, 8]"; return false; }
+  if (c->token_merge > 1 && (c->image_size / c->patch_size) % c->token_merge != 0) {
+    *why = "floor(image_size / patch_size) must be a multiple of token_merge";
+    return false;
+  }
 
   d->S = c->image_size; d->p = c->patch_size; d->C = c->channels;
   d->g = d->S / d->p; d->P = d->g * d->g; d->T = d->P + c->has_cls;
@@ -98,7 +106,11 @@ bool derive(const vit_config_t* c, Dims* d, const char** why) {
   d->proj_layers = c->proj_layers;
   d->proj_dims[0] = c->proj_dims[0]; d->proj_dims[1] = c->proj_dims[1];
   d->proj0_ld = c->proj_layers == 2 ? (int)round_up(c->proj_dims[0], 64) : 0;
-  d->out_dim = c->proj_layers ? c->proj_dims[c->proj_layers - 1] : d->D;
+  d->merge = c->token_merge > 1 ? c->token_merge : 1;
+  d->T_out = d->merge > 1 ? (d->g / d->merge) * (d->g / d->merge) : d->T;
+  d->pin = d->merge * d->merge * d->D;
+  d->pin_ld = d->merge > 1 ? (int)round_up(d->pin, 64) : d->Dp;
+  d->out_dim = c->proj_layers ? c->proj_dims[c->proj_layers - 1] : d->pin;
   d->bf16 = c->dtype == VIT_DTYPE_BF16; d->es = d->bf16 ? 2 : 4;
   d->eps = c->ln_eps; d->has_cls = c->has_cls; d->final_ln = c->final_ln;
   return true;
@@ -109,7 +121,7 @@ size_t weight_count(const Dims& d) {
   n += D * d.Kp + D + (d.has_cls ? D : 0) + (size_t)d.T * D;
   n += (size_t)d.L * (2 * D + 3 * D * D + 3 * D + D * D + D + 2 * D + M * D + M + D * M + D);
   if (d.final_ln) n += 2 * D;
-  size_t in = D;
+  size_t in = d.pin;
   for (int i = 0; i < d.proj_layers; ++i) { n += (size_t)d.proj_dims[i] * in + d.proj_dims[i]; in = d.proj_dims[i]; }
   return n;
 }
@@ -341,7 +353,7 @@ vit_status_t vit_encoder_create(const vit_config_t* cfg, const float* weights, s
       add_vec(&e->lnf_g, take(d.D), d.D);
       add_vec(&e->lnf_b, take(d.D), d.D);
     }
-    int in = d.D, in_ld = d.Dp;
+    int in = d.pin, in_ld = d.pin_ld;
     for (int i = 0; i < d.proj_layers; ++i) {
       const int dout = d.proj_dims[i];
       const float* W = take((size_t)dout * in);
@@ -398,7 +410,8 @@ namespace {
 // Workspace carving, shared by query and encode.
 struct Workspace {
   int64_t n_tok, Mpad, patch_rows_pad, max_work;
-  size_t off_x, off_h, off_qkv, off_o, off_u, off_tables, table_bytes, total;
+  int64_t n_out, out_pad;
+  size_t off_x, off_h, off_qkv, off_o, off_u, off_tables, off_merge, table_bytes, total;
 };
 
 void plan_workspace(const Dims& d, int64_t n_tiles, Workspace* w) {
@@ -419,6 +432,10 @@ void plan_workspace(const Dims& d, int64_t n_tiles, Workspace* w) {
   w->off_u = carve(u_elems * d.es);
   w->table_bytes = (size_t)(d.L > d.L_loc ? 2 : 1) * w->max_work * sizeof(AttnWork);
   w->off_tables = carve(w->table_bytes);
+  w->n_out = n_tiles * d.T_out;
+  w->out_pad = round_up(std::max<int64_t>(w->n_out, 1), pad);
+  // down-sampled rows ahead of the projector (with no projector they go straight to the output)
+  w->off_merge = carve(d.merge > 1 && d.proj_layers > 0 ? (size_t)w->out_pad * d.pin_ld * d.es : 0);
   w->total = off;
 }
 
@@ -435,9 +452,9 @@ vit_status_t vit_encoder_query(const vit_encoder_t* e, int32_t n_tiles, int32_t 
     return fail(VIT_EINVAL, "vit_encoder_query: n_tiles * tokens_per_tile exceeds the 2^31 row limit");
   Workspace w;
   plan_workspace(e->d, n_tiles, &w);
-  if (n_tokens) *n_tokens = w.n_tok;
+  if (n_tokens) *n_tokens = w.n_out;
   if (out_dim) *out_dim = e->d.out_dim;
-  if (out_bytes) *out_bytes = (size_t)w.n_tok * e->d.out_dim * e->d.es;
+  if (out_bytes) *out_bytes = (size_t)w.n_out * e->d.out_dim * e->d.es;
   if (workspace_bytes) *workspace_bytes = n_tiles ? w.total : 0;
   return VIT_OK;
 }
@@ -468,7 +485,7 @@ vit_status_t vit_encode_packed(vit_encoder_t* e, const float* pixels, const int3
     request_token_offsets[0] = 0;
     for (int r = 0; r < n_requests; ++r) {
       img += images_per_request[r];
-      request_token_offsets[r + 1] = (int64_t)tile_offsets[img] * d.T;
+      request_token_offsets[r + 1] = (int64_t)tile_offsets[img] * d.T_out;
     }
   }
   if (n_tiles == 0) return VIT_OK;
@@ -478,7 +495,7 @@ vit_status_t vit_encode_packed(vit_encoder_t* e, const float* pixels, const int3
 
   Workspace w;
   plan_workspace(d, n_tiles, &w);
-  const size_t out_need = (size_t)w.n_tok * d.out_dim * d.es;
+  const size_t out_need = (size_t)w.n_out * d.out_dim * d.es;
   if (out_capacity_bytes < out_need)
     return fail(VIT_ECAPACITY, "vit_encode_packed: out_tokens holds %zu bytes, %zu needed", out_capacity_bytes, out_need);
   if (workspace_bytes < w.total)
@@ -578,16 +595,30 @@ vit_status_t vit_encode_packed(vit_encoder_t* e, const float* pixels, const int3
     HIP_TRY(gemm(L.w2, u, d.Mp, n_tok, EPI_BIAS_RESIDUAL, nullptr, d.D, x));
   }
 
-  // ---- final LayerNorm and projector
-  if (d.proj_layers == 0) {
-    HIP_TRY(layernorm(e->lnf_g, e->lnf_b, d.final_ln, out_tokens, d.D, d.D));
-  } else {
-    HIP_TRY(layernorm(e->lnf_g, e->lnf_b, d.final_ln, h, d.Dp, d.Dp));
-    if (d.proj_layers == 1) {
-      HIP_TRY(gemm(e->proj[0], h, d.Dp, n_tok, EPI_BIAS, out_tokens, d.out_dim, nullptr));
+  // ---- final LayerNorm, token down-sampling and projector
+  if (d.merge == 1) {
+    if (d.proj_layers == 0) {
+      HIP_TRY(layernorm(e->lnf_g, e->lnf_b, d.final_ln, out_tokens, d.D, d.D));
     } else {
-      HIP_TRY(gemm(e->proj[0], h, d.Dp, n_tok, EPI_BIAS_GELU, u, d.proj0_ld, nullptr));
-      HIP_TRY(gemm(e->proj[1], u, d.proj0_ld, n_tok, EPI_BIAS, out_tokens, d.out_dim, nullptr));
+      HIP_TRY(layernorm(e->lnf_g, e->lnf_b, d.final_ln, h, d.Dp, d.Dp));
+    }
+  } else {
+    // normalised rows -> h, then m x m neighbours side by side: straight into the output, or into the
+    // projector's operand buffer
+    HIP_TRY(layernorm(e->lnf_g, e->lnf_b, d.final_ln, h, d.Dp, d.Dp));
+    void* dst = d.proj_layers == 0 ? out_tokens : (void*)(ws + w.off_merge);
+    const int dst_ld = d.proj_layers == 0 ? d.pin : d.pin_ld;
+    ProfScope ps(e, s, VIT_PROF_PATCHIFY);
+    HIP_TRY(launch_token_merge(h, d.Dp, dst, dst_ld, (int)n_tiles, d.T, d.has_cls, d.g, d.merge, d.D, d.es, s));
+  }
+  if (d.proj_layers > 0) {
+    const void* pin = d.merge == 1 ? h : (const void*)(ws + w.off_merge);
+    const int n_out = (int)w.n_out;
+    if (d.proj_layers == 1) {
+      HIP_TRY(gemm(e->proj[0], pin, d.pin_ld, n_out, EPI_BIAS, out_tokens, d.out_dim, nullptr));
+    } else {
+      HIP_TRY(gemm(e->proj[0], pin, d.pin_ld, n_out, EPI_BIAS_GELU, u, d.proj0_ld, nullptr));
+      HIP_TRY(gemm(e->proj[1], u, d.proj0_ld, n_out, EPI_BIAS, out_tokens, d.out_dim, nullptr));
     }
   }
   return VIT_OK;

@@ -71,7 +71,7 @@ def check_case(cfg, tiles_per_image, ipr, wseed=0, pseed=1, wscale=1.0, oracle_d
     want, rto_want = O.vit_oracle_encode(cfg, weights, px, ipr, to, dtype=oracle_dtype, images=images)
     say(f"    {label}: gpu {t1 - t0:.1f}s oracle {time.time() - t1:.1f}s")
     assert list(rto) == list(rto_want)
-    T = O.tokens_per_tile(cfg)
+    T = O.out_tokens_per_tile(cfg)
     if images is None:
         assert_parity(got, want, cfg["dtype"], label)
     else:

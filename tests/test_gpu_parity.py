@@ -34,6 +34,30 @@ def test_large_weights_sharpen_attention(name, scale):
     check_case(gen.get_config(name), [2, 3], [2], wscale=scale, label=f"{name} x{scale}")
 
 
+@pytest.mark.parametrize("name,tpi,ipr", [
+    ("test_merge_bf16", [1, 3, 2], [2, 0, 1]),     # 2 x 2 down-sampling, CLS dropped, 2-layer projector
+    ("test_merge_fp32", [2, 1], [1, 1]),
+    ("test_merge3_bf16", [1, 2, 1, 4], [4]),        # 3 x 3, no CLS, no final LN, no projector: straight to the output
+])
+def test_token_downsampling_matches_oracle(name, tpi, ipr):
+    """Token down-sampling between the final LayerNorm and the projector (Table 1: 448-px tiles -> 256 tokens)."""
+    cfg = gen.get_config(name)
+    say(f"case {name} tiles/image {tpi}")
+    got, want = check_case(cfg, tpi, ipr, label=name)
+    assert got.shape == (sum(tpi) * gen.out_tokens_per_tile(cfg), want.shape[1])
+
+
+def test_token_downsampling_many_tiles_bf16():
+    """A 448-px-style grid at reduced width: 16 x 16 patches + CLS = 257 tokens per tile -> 64 output tokens
+    of 4 * 256 channels; 40 tiles, so the projector's operand has several row tiles and a ragged tail."""
+    cfg = gen.get_config("test_merge_bf16")
+    cfg.update(image_size=112, hidden=256, heads=4, mlp=512, proj_dims=(320, 192))
+    tpi = [5, 1, 5, 3, 5, 1, 5, 5, 5, 5]
+    say("case down-sampling, 40 tiles")
+    got, _ = check_case(cfg, tpi, [3, 0, 7], images=[0, 1, 3, 9], label="merge40")
+    assert got.shape == (40 * 64, 192)
+
+
 def test_ragged_many_tiles_bf16():
     """Enough rows for several 256-row GEMM tiles plus a ragged tail; heavy-tailed request sizes."""
     cfg = gen.get_config("test_medium_bf16")          # 226 tokens per tile
@@ -175,7 +199,6 @@ def test_profile_counters():
     enc.close()
 
 
-@pytest.mark.gpu
 def test_mfma_ceiling_probe_reports_a_plausible_rate():
     import paper_2502_00937_amd as V
 
@@ -186,7 +209,6 @@ def test_mfma_ceiling_probe_reports_a_plausible_rate():
     assert 500.0 < t < 2600.0 and 500.0 < c < 2600.0  # below the nominal 2.5 PFLOP/s (+ clock tolerance), far above VALU rates
 
 
-@pytest.mark.gpu
 def test_routed_and_packed_launches_match_the_oracle_per_request():
     """Requests of 3, 1, 4 and 2 images are routed image by image over two instances (here: two launch
     queues on the one GPU), packed into launches of at most 3 images and encoded; every image's tokens
@@ -237,7 +259,6 @@ def test_routed_and_packed_launches_match_the_oracle_per_request():
     assert seen == sum(len(r) for r in requests) and router.pending == [0, 0]
 
 
-@pytest.mark.gpu
 def test_pull_style_handoff_assembles_a_request_encoded_in_two_launches():
     """A request of four images is encoded in two launches (images 0, 2 and images 1, 3, as a router
     might split it) interleaved with another request; the consumer pulls when all four are published
