@@ -40,9 +40,10 @@ def flops(cfg, tile_offsets):
     tpi = np.diff(np.asarray(tile_offsets, dtype=np.int64))
     n_tiles = int(tpi.sum())
     gemm = n_tiles * (2.0 * P * K * D + (L_loc + L_glob) * (2.0 * T * D * 3 * D + 2.0 * T * D * D + 4.0 * T * D * M))
-    d_in = D
+    m = max(cfg["token_merge"], 1)
+    d_in, t_out = D * m * m, (T if m == 1 else (g // m) ** 2)  # the projector sees the down-sampled tokens
     for i in range(cfg["proj_layers"]):
-        gemm += n_tiles * 2.0 * T * d_in * cfg["proj_dims"][i]
+        gemm += n_tiles * 2.0 * t_out * d_in * cfg["proj_dims"][i]
         d_in = cfg["proj_dims"][i]
     attn = n_tiles * L_loc * 4.0 * T * T * D + float(sum(L_glob * 4.0 * (n * T) * (n * T) * D for n in tpi))
     return gemm + attn, gemm, attn
@@ -131,7 +132,7 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=10)
     ap.add_argument("--warmup", type=int, default=3)
-    ap.add_argument("--workload", default="cfg3", choices=["cfg1", "cfg2", "cfg3", "cfg4", "cfg5"])
+    ap.add_argument("--workload", default="cfg3", choices=["cfg1", "cfg2", "cfg3", "cfg4", "cfg5", "cfg6"])
     ap.add_argument("--cpu-sample", type=int, default=12, help="images the CPU oracle encodes (0 = skip)")
     ap.add_argument("--no-kernel-events", action="store_true", help="time the steps without per-kernel events")
     ap.add_argument("--sweep", action="store_true",
@@ -203,8 +204,11 @@ def main():
             "workload": {"cfg1": "tiny ViT fp32, 4 images", "cfg2": "ViT-L/14-336 + projector, 8 images",
                          "cfg3": "ViT-L/14-336 + 2-layer projector, ragged batch: 64 requests / 260 images, one launch",
                          "cfg4": "SigLIP-style 384px, 128 images / 591 tiles",
-                         "cfg5": "ViT-H/14-560, 32 images x 4 tiles, 32 local + 8 global layers"}[args.workload],
+                         "cfg5": "ViT-H/14-560, 32 images x 4 tiles, 32 local + 8 global layers",
+                         "cfg6": "6B-class ViT on 448px tiles, 2x2 token down-sampling to 256 tokens per tile, "
+                                 "8 images / 36 tiles"}[args.workload],
             "requests": int(len(ipr)), "images": n_images, "tiles": n_tiles, "tokens": int(n_tok),
+            "encoder_tokens": n_tiles * T,
             "weights": "seeded N(0, 0.02), bf16-rounded", "pixels": "seeded U[-1,1), resident in HBM",
         },
         "ms_per_step_median": step_ms[len(step_ms) // 2], "ms_per_step_min": step_ms[0],
@@ -235,7 +239,7 @@ def main():
         # LayerNorm passes: each reads fp32 [tokens, D] and writes the operand type
         es = 2 if cfg["dtype"] == "bf16" else 4
         ln_n = prof["layernorm"][1] // args.steps
-        ln_bytes = ln_n * n_tok * cfg["hidden"] * (4 + es)
+        ln_bytes = ln_n * n_tiles * T * cfg["hidden"] * (4 + es)  # every encoder token, before any down-sampling
         result["layernorm_gbs"] = ln_bytes / (fam_ms["layernorm"] * 1e-3) / 1e9 if fam_ms["layernorm"] > 0 else None
     enc.close()
     if args.cpu_sample > 0:

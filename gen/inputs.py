@@ -84,6 +84,10 @@ def make_workload(name: str):
         cfg, ipr, tpi = get_config("cfg4_siglip_384"), [1] * 128, list(CFG4_TILES_PER_IMAGE)
     elif name == "cfg5":
         cfg, ipr, tpi = get_config("cfg5_vith14_560"), [1] * 32, [4] * 32
+    elif name == "cfg6":
+        # second workload: seven images of five 448-px tiles (Table 1: 5 x 256 tokens for an 896-px image)
+        # and one single-tile image, small enough for the oracle to encode at full width and depth
+        cfg, ipr, tpi = get_config("cfg6_6b_448"), [1] * 8, [5] * 7 + [1]
     else:
         raise KeyError(name)
     tile_offsets = np.concatenate([[0], np.cumsum(tpi)]).astype(np.int32)

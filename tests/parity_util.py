@@ -65,9 +65,14 @@ def check_case(cfg, tiles_per_image, ipr, wseed=0, pseed=1, wscale=1.0, oracle_d
             weights = gen.round_to_bf16(weights)
     to = np.concatenate([[0], np.cumsum(tiles_per_image)]).astype(np.int32)
     px = gen.make_pixels(cfg, int(to[-1]), seed=pseed)
+    big = weights.size > (1 << 30)  # progress lines for the one case whose steps take minutes
+    if big:
+        say(f"    {label}: {weights.size / 1e9:.2f} G weights generated")
     t0 = time.time()
     got, rto = gpu_encode(cfg, weights, px, ipr, to)
     t1 = time.time()
+    if big:
+        say(f"    {label}: gpu done in {t1 - t0:.1f}s, oracle running")
     want, rto_want = O.vit_oracle_encode(cfg, weights, px, ipr, to, dtype=oracle_dtype, images=images)
     say(f"    {label}: gpu {t1 - t0:.1f}s oracle {time.time() - t1:.1f}s")
     assert list(rto) == list(rto_want)

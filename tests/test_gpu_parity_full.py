@@ -3,6 +3,8 @@
 The GPU encodes the whole batch; the oracle encodes whole images sampled from it (an image's
 tokens depend on its own tiles only), because the full batches are 100+ TFLOP.
 """
+import os
+
 import numpy as np
 import pytest
 
@@ -56,3 +58,15 @@ def test_cfg5_local_global_sampled():
     say(f"case cfg5 (32 images x 4 tiles), oracle on image {images}")
     got, _ = check_case(cfg, tpi, ipr, images=images, oracle_dtype=np.float32, label="cfg5")
     assert got.shape == (128 * 1601, 1280)
+
+
+@pytest.mark.skipif(os.environ.get("VITENC_TEST_6B") != "1",
+                    reason="second workload at full size: 5.65 G weights (23 GB fp32 on the host, two minutes to "
+                           "generate) and a 12 TFLOP fp32 oracle pass; run with VITENC_TEST_6B=1")
+def test_cfg6_6b_downsampled_sampled():
+    cfg, ipr, tpi = _workload("cfg6")
+    images = [7]               # the single-tile image
+    assert tpi[7] == 1
+    say(f"case cfg6 (8 images / 36 tiles, 6B-class, 2x2 down-sampling), oracle on image {images}")
+    got, _ = check_case(cfg, tpi, ipr, images=images, oracle_dtype=np.float32, label="cfg6")
+    assert got.shape == (36 * 256, 6144)
