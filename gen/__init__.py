@@ -9,6 +9,7 @@ from .inputs import (  # noqa: F401
     CFG3_IMAGES_PER_REQUEST,
     CFG4_TILES_PER_IMAGE,
     make_arrivals,
+    make_image_u8,
     make_pixels,
     make_weights,
     make_workload,

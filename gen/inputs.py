@@ -68,6 +68,19 @@ def make_pixels(cfg: dict, n_tiles: int, seed: int = 1) -> np.ndarray:
     return px
 
 
+def make_image_u8(height: int, width: int, channels: int = 3, seed: int = 0) -> np.ndarray:
+    """[H, W, C] uint8 raw image: smooth low-frequency content plus noise, so that interpolation between
+    neighbouring pixels is neither trivial nor pure noise."""
+    rng = np.random.default_rng(seed)
+    y, x = np.mgrid[0:height, 0:width].astype(np.float32)
+    img = np.empty((height, width, channels), dtype=np.float32)
+    for c in range(channels):
+        fy, fx, ph = rng.uniform(0.01, 0.2), rng.uniform(0.01, 0.2), rng.uniform(0, 6.28)
+        img[..., c] = 127.5 + 90.0 * np.sin(fy * y + fx * x + ph)
+    img += rng.normal(0.0, 20.0, img.shape).astype(np.float32)
+    return np.clip(np.rint(img), 0, 255).astype(np.uint8)
+
+
 def make_workload(name: str):
     """Return (cfg, images_per_request, tile_offsets) for a named benchmark workload.
 
@@ -96,7 +109,7 @@ def make_workload(name: str):
 
 __all__ = [
     "CFG3_IMAGES_PER_REQUEST", "CFG4_TILES_PER_IMAGE", "round_to_bf16", "make_weights",
-    "make_pixels", "make_workload", "tokens_per_tile",
+    "make_pixels", "make_workload", "make_image_u8", "tokens_per_tile",
 ]
 
 
