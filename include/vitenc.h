@@ -190,6 +190,31 @@ vit_status_t vit_handoff_pull(vit_handoff_t* h, int64_t request_id, void* dst, s
 vit_status_t vit_handoff_release(vit_handoff_t* h, int64_t request_id);
 
 /*
+ * Image preprocessing on the GPU (paper Sec. 2, "Image Preprocessing": resize, rescale and
+ * normalise the raw image, segment it into tiles), producing exactly the `pixels` operand of
+ * vit_encode_packed.
+ *   image       DEVICE, [height, width, channels] uint8, channels interleaved, 1 <= channels <= 4.
+ *   The image is resized to (grid_rows * tile_size) x (grid_cols * tile_size) by bilinear
+ *   interpolation (pixel centres at half-integers: source coordinate (o + 0.5) * in/out - 0.5,
+ *   clamped below at 0, last pixel repeated at the far edge; no low-pass filter when shrinking),
+ *   scaled by 1/255, normalised per channel as (v - mean[c]) / std[c], and cut into
+ *   grid_rows * grid_cols tiles in row-major tile order.  thumbnail != 0 appends one more tile:
+ *   the whole image resized to tile_size x tile_size.
+ *   mean, std   HOST, [channels]; std > 0.
+ *   out_pixels  DEVICE, [n_tiles, channels, tile_size, tile_size] fp32, n_tiles = grid_rows *
+ *               grid_cols (+ 1), 4-byte aligned; out_capacity_bytes is its size.
+ *   stream      hipStream_t (NULL = default stream); the call is asynchronous on it and runs on the
+ *               calling thread's current device, where both buffers must live.
+ * Choosing the tile grid from the image size, padding and tile-level augmentation stay with the caller.
+ * Errors: VIT_EINVAL (NULL, non-positive sizes, channels > 4, more than 65534 tiles, std <= 0),
+ *         VIT_ECAPACITY (nothing launched), VIT_EDEVICE.
+ */
+vit_status_t vit_preprocess_tiles(const uint8_t* image, int32_t height, int32_t width, int32_t channels,
+                                  int32_t tile_size, int32_t grid_rows, int32_t grid_cols, int32_t thumbnail,
+                                  const float* mean, const float* std, float* out_pixels,
+                                  size_t out_capacity_bytes, void* stream);
+
+/*
  * Measurement aid (no part of the encode path): runs a register-only bf16 MFMA loop
  * (v_mfma_f32_32x32x16_bf16, two waves per SIMD, no memory traffic) on `device` for about
  * `seconds` (0 < seconds <= 2) on the null stream and writes the sustained rate in TFLOP/s

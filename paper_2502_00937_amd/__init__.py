@@ -9,10 +9,12 @@ from .binding import (  # noqa: F401
     VitError,
     lib_path,
     load_library,
+    preprocess_tiles,
     vit_encode_packed,
     vit_encoder_create,
     vit_encoder_destroy,
     vit_encoder_query,
     vit_mfma_ceiling,
+    vit_preprocess_tiles,
     vit_weight_count,
 )

@@ -73,6 +73,10 @@ def load_library():
     lib.vit_handoff_pull.argtypes = [C.c_void_p, C.c_int64, C.c_void_p, C.c_size_t, C.c_void_p, C.POINTER(C.c_size_t)]
     lib.vit_handoff_release.restype = C.c_int
     lib.vit_handoff_release.argtypes = [C.c_void_p, C.c_int64]
+    lib.vit_preprocess_tiles.restype = C.c_int
+    lib.vit_preprocess_tiles.argtypes = [C.c_void_p, C.c_int32, C.c_int32, C.c_int32, C.c_int32, C.c_int32, C.c_int32,
+                                         C.c_int32, C.POINTER(C.c_float), C.POINTER(C.c_float), C.c_void_p, C.c_size_t,
+                                         C.c_void_p]
     lib.vit_mfma_ceiling.restype = C.c_int
     lib.vit_mfma_ceiling.argtypes = [C.c_int, C.c_double, C.c_int32, C.POINTER(C.c_double)]
     lib.vit_profile_read.restype = C.c_int
@@ -132,6 +136,33 @@ def vit_encode_packed(handle: int, pixels_ptr: int, images_per_request, tile_off
                                             to.ctypes.data, out_ptr, out_capacity_bytes, rto.ctypes.data,
                                             workspace_ptr, workspace_bytes, stream))
     return rto
+
+
+def vit_preprocess_tiles(image_ptr: int, height: int, width: int, channels: int, tile_size: int, grid_rows: int,
+                         grid_cols: int, thumbnail: bool, mean, std, out_ptr: int, out_capacity_bytes: int,
+                         stream: int = 0) -> None:
+    """Raw pointers in, nothing returned: resize + rescale + normalise + tile on the current device."""
+    m = (C.c_float * channels)(*[float(v) for v in mean])
+    sd = (C.c_float * channels)(*[float(v) for v in std])
+    _check(load_library().vit_preprocess_tiles(C.c_void_p(image_ptr), height, width, channels, tile_size, grid_rows,
+                                               grid_cols, 1 if thumbnail else 0, m, sd, C.c_void_p(out_ptr),
+                                               out_capacity_bytes, C.c_void_p(stream)))
+
+
+def preprocess_tiles(image, tile_size: int, grid_rows: int, grid_cols: int, thumbnail: bool, mean, std, out=None):
+    """image: torch uint8 [H, W, C] on the GPU -> fp32 [n_tiles, C, S, S] (the encoder's `pixels`)."""
+    import torch
+
+    assert image.is_cuda and image.dtype == torch.uint8 and image.is_contiguous() and image.dim() == 3
+    H, W, Cn = image.shape
+    n_tiles = grid_rows * grid_cols + (1 if thumbnail else 0)
+    if out is None:
+        out = torch.empty((n_tiles, Cn, tile_size, tile_size), dtype=torch.float32, device=image.device)
+    assert out.is_cuda and out.dtype == torch.float32 and out.is_contiguous()
+    with torch.cuda.device(image.device):
+        vit_preprocess_tiles(image.data_ptr(), H, W, Cn, tile_size, grid_rows, grid_cols, thumbnail, mean, std,
+                             out.data_ptr(), out.numel() * 4, torch.cuda.current_stream().cuda_stream)
+    return out
 
 
 def vit_mfma_ceiling(device: int = 0, seconds: float = 0.1, random_operands: bool = True) -> float:

@@ -10,7 +10,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 BUILD = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libvitenc.so")
-SOURCES = ["vitenc_api.hip", "gemm_bf16.hip", "attention_bf16.hip", "rowops.hip", "fp32_path.hip", "handoff.hip"]
+SOURCES = ["vitenc_api.hip", "gemm_bf16.hip", "attention_bf16.hip", "rowops.hip", "fp32_path.hip", "handoff.hip", "preprocess.hip"]
 FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-fvisibility=hidden",
     "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",

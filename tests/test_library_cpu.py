@@ -40,6 +40,25 @@ def test_mfma_ceiling_rejects_bad_arguments_before_touching_a_device():
     assert out.value == -1.0
 
 
+def test_preprocess_rejects_bad_arguments_before_touching_a_device():
+    import ctypes as C
+
+    lib = V.load_library()
+    m, sd = (C.c_float * 3)(0.5, 0.5, 0.5), (C.c_float * 3)(0.2, 0.2, 0.2)
+    fake = C.c_void_p(4096)  # never dereferenced: every call below is refused on the host
+    ok = dict(h=8, w=8, c=3, s=4, r=1, k=1)
+
+    def call(img=fake, out=fake, mean=m, std=sd, cap=1 << 20, **kw):
+        a = dict(ok, **kw)
+        return lib.vit_preprocess_tiles(img, a["h"], a["w"], a["c"], a["s"], a["r"], a["k"], 0, mean, std, out, cap, None)
+
+    assert call(img=None) == -1 and call(out=None) == -1 and call(mean=None) == -1 and call(std=None) == -1
+    assert call(h=0) == -1 and call(c=5) == -1 and call(s=0) == -1 and call(r=0) == -1 and call(r=300, k=300) == -1
+    assert call(std=(C.c_float * 3)(0.2, 0.0, 0.2)) == -1
+    assert call(cap=4 * 3 * 4 * 4 - 1) == -3                 # VIT_ECAPACITY, nothing launched
+    assert b"out_pixels holds" in lib.vit_last_error()
+
+
 def test_struct_matches_header_field_order():
     text = open(os.path.join(ROOT, "include", "vitenc.h")).read()
     body = text[text.index("typedef struct {"):text.index("} vit_config_t;")]
