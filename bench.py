@@ -26,7 +26,7 @@ HBM_PEAK_GBS = 8000.0
 # HBM-side bytes of all matrix-product launches of ONE cfg3 step, from the two rocprofv3 --pmc runs
 # (FETCH_SIZE x 2.0 + WRITE_SIZE x 1.0, factors from the copy calibration) summarised in
 # profiles/kernels_cfg3_ragged_hbm_traffic.md.  A profile figure, not measured by this script.
-GEMM_TRAFFIC_BYTES_PER_STEP = {"cfg3": 257.9e9}
+GEMM_TRAFFIC_BYTES_PER_STEP = {"cfg3": 257.4e9}
 
 
 def flops(cfg, tile_offsets):
@@ -101,6 +101,19 @@ def sweep(args, torch, gen, V):
     timed(260, np.ones(260, dtype=np.int32), "cfg3 as 260 single-image requests")
     timed(260, np.asarray([260], dtype=np.int32), "cfg3 as one request of 260 images")
     enc.close()
+
+    # GPU preprocessing (Sec. 2): Table 1's example, an 896 x 896 image -> 2 x 2 tiles of 448 + a thumbnail
+    img = torch.from_numpy(gen.make_image_u8(896, 896, 3, seed=2)).cuda()
+    tiles = V.preprocess_tiles(img, 448, 2, 2, True, (0.48, 0.45, 0.41), (0.27, 0.26, 0.28))
+    torch.cuda.synchronize()
+    reps = 200
+    t0 = time.perf_counter()
+    for _ in range(reps):
+        V.preprocess_tiles(img, 448, 2, 2, True, (0.48, 0.45, 0.41), (0.27, 0.26, 0.28), out=tiles)
+    torch.cuda.synchronize()
+    us = (time.perf_counter() - t0) / reps * 1e6
+    print(json.dumps({"preprocess": "896x896x3 uint8 -> 5 tiles of 448 (fp32)", "us_per_image": us,
+                      "images_per_s": 1e6 / us, "gb_per_s": (img.numel() + tiles.numel() * 4) / us / 1e3}))
 
     # Stage profile -> maximum batch and capacity under a latency SLO (Sec. 4.2), then the two routing
     # policies of Sec. 4.3 on a seeded heavy-tailed request stream, four Image Instances modelled with
