@@ -314,3 +314,38 @@ def test_pull_style_handoff_assembles_a_request_encoded_in_two_launches():
     h.release(6)
     h.close()
     enc.close()
+
+
+def _random_case(seed):
+    """A seeded random small encoder + batch: shapes the fixed presets do not hit (odd patch grids, mlp and
+    projector widths that are multiples of 8 only, every head-dim instantiation, down-sampling factors)."""
+    rng = np.random.default_rng(1000 + seed)
+    p = int(rng.choice([4, 7, 14]))
+    g = int(rng.integers(3, 10))
+    dh = int(rng.choice([64, 72, 80, 96, 128]))
+    heads = int(rng.integers(1, 4))
+    merge = int(rng.choice([m for m in (1, 1, 2, 3) if g % m == 0]))
+    if seed % 3 == 0:  # every third case down-samples for sure
+        g, merge = [(4, 2), (6, 3), (8, 2), (6, 2)][(seed // 3) % 4]
+    n_proj = int(rng.integers(0, 3))
+    cfg = {
+        "image_size": g * p + int(rng.integers(0, p)), "patch_size": p, "channels": 3,
+        "hidden": dh * heads, "heads": heads, "mlp": 8 * int(rng.integers(8, 80)),
+        "layers_local": int(rng.integers(1, 3)), "layers_global": int(rng.integers(0, 2)),
+        "has_cls": int(rng.integers(0, 2)), "final_ln": int(rng.integers(0, 2)), "ln_eps": 1e-6,
+        "proj_layers": n_proj, "proj_dims": tuple(8 * int(rng.integers(4, 40)) for _ in range(n_proj)),
+        "dtype": "fp32" if seed % 5 == 4 else "bf16", "token_merge": merge,
+    }
+    n_images = int(rng.integers(1, 6))
+    tpi = [int(rng.integers(1, 5)) for _ in range(n_images)]
+    # split the images over requests, with an empty request in between
+    cut = int(rng.integers(0, n_images + 1))
+    ipr = [cut, 0, n_images - cut]
+    return cfg, tpi, ipr
+
+
+@pytest.mark.parametrize("seed", range(12))
+def test_random_small_encoders_match_oracle(seed):
+    cfg, tpi, ipr = _random_case(seed)
+    say(f"case random {seed}: {cfg} tiles/image {tpi} images/request {ipr}")
+    check_case(cfg, tpi, ipr, wseed=seed, pseed=seed + 50, label=f"random{seed}")
