@@ -76,12 +76,20 @@ def test_weight_count_matches_generator_for_all_presets():
 def test_weight_count_rejects_bad_configs():
     base = gen.get_config("test_small_bf16")
     for key, val in [("heads", 3), ("hidden", 0), ("patch_size", 0), ("proj_layers", 3), ("mlp", 7),
-                     ("hidden", 20), ("has_cls", 2), ("layers_local", -1), ("ln_eps", float("nan"))]:
+                     ("hidden", 20), ("has_cls", 2), ("layers_local", -1), ("ln_eps", float("nan")),
+                     ("token_merge", 3), ("token_merge", -1), ("token_merge", 9)]:  # 56/14 = 4 is no multiple of 3
         cfg = dict(base)
         cfg[key] = val
         if key == "proj_layers":
             cfg["proj_dims"] = (8, 8)
         assert V.vit_weight_count(cfg) == 0, (key, val)
+
+
+def test_token_merge_changes_the_projector_input_only():
+    base = gen.get_config("test_small_bf16")            # 4 x 4 patches, D = 128, projector 128 -> 192 -> 160
+    merged = dict(base, token_merge=2)
+    assert V.vit_weight_count(merged) - V.vit_weight_count(base) == 192 * 3 * 128
+    assert V.vit_weight_count(dict(base, token_merge=0)) == V.vit_weight_count(base)   # 0 and 1 both mean none
 
 
 def test_create_rejects_null_and_bad_arguments_without_a_device():
