@@ -225,7 +225,8 @@ def main():
             "weights": "seeded N(0, 0.02), bf16-rounded", "pixels": "seeded U[-1,1), resident in HBM",
         },
         "ms_per_step_median": step_ms[len(step_ms) // 2], "ms_per_step_min": step_ms[0],
-        "tokens_per_s": n_tok / (ms_per_step * 1e-3),
+        "tokens_per_s": n_tiles * T / (ms_per_step * 1e-3),  # encoder tokens; differs from the output only with token_merge
+        "output_tokens_per_s": n_tok / (ms_per_step * 1e-3),
         "tiles_per_s": n_tiles / (ms_per_step * 1e-3),
         "tflops": total_f / (ms_per_step * 1e-3) / 1e12,
         "pct_bf16_peak": 100.0 * total_f / (ms_per_step * 1e-3) / 1e12 / PEAK_BF16_TFLOPS,
