@@ -66,27 +66,38 @@ def test_ragged_many_tiles_bf16():
     check_case(cfg, tpi, [1, 0, 4, 3], label="ragged")
 
 
-def test_wide_batch_reaches_persistent_gemm():
-    """Enough token rows (160 tiles x 226 = 36 160) that every matrix product of this small network takes the
-    persistent 256 x 256 kernel, including a ragged last row block, K of 4 and 8 k-stages and a column band
-    that is narrower than a tile group.  The oracle encodes sampled images (first, a multi-tile one, last)."""
+def test_wide_batch_mixes_both_gemm_kernels():
+    """160 tiles x 226 = 36 160 token rows (142 row blocks of 256, ragged last one): the QKV product (three tile
+    columns, 426 tiles) takes the persistent 256 x 256 kernel, the others (one or two tile columns) the
+    128 x 128 ring kernel with two-stage rings; K of 4 and 8 k-stages.  The oracle encodes sampled images
+    (first, a multi-tile one, last)."""
     cfg = gen.get_config("test_medium_bf16")
     tpi = [1, 4, 1, 1, 2, 7, 1, 3] * 8           # 64 images, 160 tiles
-    say("case wide batch (160 tiles, persistent GEMM)")
+    say("case wide batch (160 tiles, both GEMM kernels)")
     got, _ = check_case(cfg, tpi, [len(tpi)], images=[0, 5, 63], label="wide")
     assert got.shape[0] == 160 * 226
 
 
 def test_odd_k_stage_counts_and_narrow_column_bands_on_the_persistent_gemm():
-    """340 tiles x 197 tokens = 66 980 rows (262 row blocks), so even the products with a single tile column
-    take the persistent kernel.  K = 64, 192 and 320 are 1, 3 and 5 k-stages: the two LDS stages change roles
-    from one tile to the next.  N = 576, 192 and 320 are three, one and two tile columns: a band with an idle
-    column and the 32 x 1 and 16 x 2 tile groups."""
+    """500 tiles x 197 tokens = 98 500 rows (385 row blocks), so even the products with a single tile column
+    reach the persistent kernel's threshold of 384 tiles.  K = 64, 192 and 320 are 1, 3 and 5 k-stages: the two
+    LDS stages change roles from one tile to the next.  N = 576, 192 and 320 are three, one and two tile
+    columns: a band with an idle column and the 32 x 1 and 16 x 2 tile groups."""
     cfg = gen.get_config("test_oddk_bf16")
-    tpi = [1] * 340
-    say("case odd k-stage counts (340 tiles, persistent GEMM)")
-    got, _ = check_case(cfg, tpi, [len(tpi)], images=[0, 171, 339], label="oddk")
-    assert got.shape[0] == 340 * 197
+    tpi = [1] * 500
+    say("case odd k-stage counts (500 tiles, persistent GEMM)")
+    got, _ = check_case(cfg, tpi, [len(tpi)], images=[0, 171, 499], label="oddk")
+    assert got.shape[0] == 500 * 197
+
+
+def test_odd_k_stage_counts_on_the_ring_gemm():
+    """The same network at 60 tiles (11 820 rows, 47 row blocks): every product takes the ring kernel, with
+    1, 3 and 5 k-stages (fewer than the ring is deep) and rings of four and of two stages."""
+    cfg = gen.get_config("test_oddk_bf16")
+    tpi = [1] * 60
+    say("case odd k-stage counts (60 tiles, ring GEMM)")
+    got, _ = check_case(cfg, tpi, [len(tpi)], images=[0, 31, 59], label="oddk-ring")
+    assert got.shape[0] == 60 * 197
 
 
 def test_packing_invariance_on_gpu():
