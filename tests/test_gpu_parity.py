@@ -192,6 +192,36 @@ def test_repeated_launches_are_deterministic():
     enc.close()
 
 
+def test_one_handle_serves_batches_of_changing_size_without_waiting():
+    """Launches of very different sizes queued back to back on one handle and one stream (the workspace is
+    reused, the pinned table slots cycle, both GEMM kernels and both ring depths take turns): every result
+    equals, bit for bit, what a fresh handle produces for that batch alone."""
+    import torch
+
+    import paper_2502_00937_amd as V
+
+    cfg = gen.get_config("test_medium_bf16")      # 226 tokens per tile
+    weights = gen.make_weights(cfg)
+    px = torch.from_numpy(gen.make_pixels(cfg, 200)).cuda()
+    batches = [[1], [3, 2, 1], [1] * 150, [2], [4] * 50, [1, 1], [7, 1], [1] * 200, [5]]
+    say(f"case changing batch sizes {[sum(b) for b in batches]} tiles")
+    enc = V.VitEncoder(cfg, weights)
+    got = []
+    for tpi in batches:                           # no synchronisation between the launches
+        to = np.concatenate([[0], np.cumsum(tpi)]).astype(np.int32)
+        out, _ = enc.encode(px[:int(to[-1])], [len(tpi)], to)
+        got.append(out)                           # a fresh output tensor per launch
+    torch.cuda.synchronize()
+    enc.close()
+    for tpi, g in zip(batches, got):
+        fresh = V.VitEncoder(cfg, weights)
+        to = np.concatenate([[0], np.cumsum(tpi)]).astype(np.int32)
+        want, _ = fresh.encode(px[:int(to[-1])], [len(tpi)], to)
+        torch.cuda.synchronize()
+        fresh.close()
+        assert torch.equal(g, want), tpi[:4]
+
+
 def test_profile_counters():
     import torch
 
