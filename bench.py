@@ -95,7 +95,7 @@ def sweep(args, torch, gen, V):
         return ms
 
     points = []
-    for n in (1, 8, 64, 260):
+    for n in (1, 2, 4, 8, 16, 32, 64, 128, 260):
         points.append((n, timed(n, np.ones(n, dtype=np.int32), "images per launch")))
     timed(260, ipr3, "cfg3 as 64 ragged requests")
     timed(260, np.ones(260, dtype=np.int32), "cfg3 as 260 single-image requests")
