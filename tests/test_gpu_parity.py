@@ -58,6 +58,19 @@ def test_token_downsampling_many_tiles_bf16():
     assert got.shape == (40 * 64, 192)
 
 
+def test_maximum_width():
+    """The widest encoder the library accepts: hidden 4096 (the LayerNorm's register budget), 32 heads of
+    128, MLP 8192 (128 k-stages), a 2 x 2 patch grid; one block keeps the weights at 0.2 G."""
+    cfg = gen.get_config("test_dh128_bf16")
+    cfg.update(image_size=28, patch_size=14, hidden=4096, heads=32, mlp=8192, layers_local=1, layers_global=0,
+               has_cls=1, proj_layers=1, proj_dims=(4096,))
+    say("case maximum width (hidden 4096, 32 heads of 128, MLP 8192)")
+    check_case(cfg, [2, 1, 3], [1, 2], label="max width")
+    import paper_2502_00937_amd as V
+
+    assert V.vit_weight_count(dict(cfg, hidden=4104, heads=27)) == 0   # 27 heads of 152: beyond both limits
+
+
 def test_ragged_many_tiles_bf16():
     """Enough rows for several 256-row GEMM tiles plus a ragged tail; heavy-tailed request sizes."""
     cfg = gen.get_config("test_medium_bf16")          # 226 tokens per tile
