@@ -27,15 +27,21 @@ assert sum(CFG3_IMAGES_PER_REQUEST) == 260 and len(CFG3_IMAGES_PER_REQUEST) == 6
 assert sum(CFG4_TILES_PER_IMAGE) == 591 and len(CFG4_TILES_PER_IMAGE) == 128
 
 
+def _round_to_bf16_inplace(a: np.ndarray) -> np.ndarray:
+    u = a.reshape(-1).view(np.uint32)  # finite inputs only: the add below cannot wrap
+    step = 1 << 26                      # in pieces, so the temporaries stay small
+    for i in range(0, u.size, step):
+        v = u[i:i + step]
+        lsb = (v >> np.uint32(16)) & np.uint32(1)
+        v += np.uint32(0x7FFF)
+        v += lsb
+        v &= np.uint32(0xFFFF0000)
+    return a
+
+
 def round_to_bf16(a: np.ndarray) -> np.ndarray:
     """Return fp32 values that are exactly representable in bfloat16 (round-to-nearest-even)."""
-    a = np.array(a, dtype=np.float32, order="C", copy=True)
-    u = a.reshape(-1).view(np.uint32)  # finite inputs only: the add below cannot wrap
-    lsb = (u >> np.uint32(16)) & np.uint32(1)
-    u += np.uint32(0x7FFF)
-    u += lsb
-    u &= np.uint32(0xFFFF0000)
-    return a
+    return _round_to_bf16_inplace(np.array(a, dtype=np.float32, order="C", copy=True))
 
 
 def make_weights(cfg: dict, seed: int = 0) -> np.ndarray:
@@ -46,15 +52,19 @@ def make_weights(cfg: dict, seed: int = 0) -> np.ndarray:
     bf16-representable fp32 so both sides consume identical weights.
     """
     rng = np.random.default_rng(seed)
-    parts = []
-    for name, shape in weight_layout(cfg):
-        w = rng.standard_normal(shape, dtype=np.float32) * np.float32(0.02)
+    layout = weight_layout(cfg)
+    sizes = [int(np.prod(shape)) for _, shape in layout]
+    flat = np.empty(sum(sizes), dtype=np.float32)  # filled in place: the largest preset has 5.65 G values
+    pos = 0
+    for (name, _), n in zip(layout, sizes):
+        w = flat[pos:pos + n]
+        rng.standard_normal(out=w, dtype=np.float32)
+        w *= np.float32(0.02)
         if name.endswith(("ln1_g", "ln2_g", "lnf_g")):
             w += np.float32(1.0)
-        parts.append(w.reshape(-1))
-    flat = np.concatenate(parts)
+        pos += n
     if cfg["dtype"] == "bf16":
-        flat = round_to_bf16(flat)
+        flat = _round_to_bf16_inplace(flat)
     return flat
 
 
