@@ -304,6 +304,10 @@ vit_status_t vit_encoder_create(const vit_config_t* cfg, const float* weights, s
   std::vector<PendingPtr> pptr;
   try {
     e->layers.resize(d.L);
+    // one allocation for the host image of the weights (padding adds a few per cent; a short estimate
+    // only means the vector grows): a 6B-class encoder is 11 GB here, and growing by doubling would
+    // hold three times that for a moment
+    ar.host.reserve((size_t)((double)weight_count(d) * d.es * 1.1) + ((size_t)64 << 20));
     const float* w = weights;
     auto take = [&](size_t n) { const float* p = w; w += n; return p; };
     auto add_linear = [&](Linear* dst, const float* W, const float* b, int rows, int cols, int N, int K,

@@ -62,7 +62,7 @@ def test_cfg5_local_global_sampled():
 
 @pytest.mark.skipif(os.environ.get("VITENC_SKIP_6B") == "1",
                     reason="VITENC_SKIP_6B=1: the second workload at full size needs 5.65 G weights (23 GB fp32, "
-                           "88 GB of host memory at the peak, a minute to generate) and a 12 TFLOP fp32 oracle pass")
+                           "34 GB of host memory at the peak, a minute to generate) and a 12 TFLOP fp32 oracle pass")
 def test_cfg6_6b_downsampled_sampled():
     cfg, ipr, tpi = _workload("cfg6")
     images = [7]               # the single-tile image
