@@ -59,6 +59,39 @@ def test_preprocess_rejects_bad_arguments_before_touching_a_device():
     assert b"out_pixels holds" in lib.vit_last_error()
 
 
+def test_header_is_valid_c99_and_cxx_and_links_from_plain_c(tmp_path):
+    """The boundary is a C ABI: the header must compile as C and as C++, and a plain C program linked against
+    the library must be able to call the host-only entry points."""
+    import shutil
+    import subprocess
+
+    if not shutil.which("gcc") or not shutil.which("g++"):
+        pytest.skip("no host compiler")
+    inc = os.path.join(ROOT, "include")
+    src = tmp_path / "use.c"
+    src.write_text(
+        '#include "vitenc.h"\n#include <stdio.h>\n'
+        "int main(void) {\n"
+        "  vit_config_t c = {56, 14, 3, 128, 2, 256, 2, 1, 1, 1, 1e-6f, 2, {192, 160}, VIT_DTYPE_BF16, 2};\n"
+        "  size_t n = vit_weight_count(&c);\n"
+        "  c.heads = 3;\n"
+        '  printf("%zu %zu %s\\n", n, vit_weight_count(&c), vit_last_error());\n'
+        "  return vit_encoder_create(&c, 0, 0, 0, 0) == VIT_EINVAL ? 0 : 1;\n"
+        "}\n")
+    subprocess.run(["gcc", "-std=c99", "-Wall", "-Wextra", "-Werror", "-pedantic", "-fsyntax-only", f"-I{inc}", str(src)],
+                   check=True)
+    cxx = tmp_path / "use.cpp"
+    cxx.write_text('#include "vitenc.h"\nint main() { return vit_weight_count(nullptr) == 0 ? 0 : 1; }\n')
+    subprocess.run(["g++", "-std=c++17", "-Wall", "-Wextra", "-Werror", "-fsyntax-only", f"-I{inc}", str(cxx)], check=True)
+    exe = tmp_path / "use"
+    libdir = os.path.dirname(V.lib_path())
+    subprocess.run(["gcc", "-std=c99", f"-I{inc}", str(src), "-o", str(exe), f"-L{libdir}", "-lvitenc",
+                    f"-Wl,-rpath,{libdir}"], check=True)
+    out = subprocess.run([str(exe)], check=True, capture_output=True, text=True).stdout.split()
+    cfg = dict(gen.get_config("test_small_bf16"), token_merge=2)
+    assert int(out[0]) == gen.weight_count(cfg) and int(out[1]) == 0
+
+
 def test_struct_matches_header_field_order():
     text = open(os.path.join(ROOT, "include", "vitenc.h")).read()
     body = text[text.index("typedef struct {"):text.index("} vit_config_t;")]
