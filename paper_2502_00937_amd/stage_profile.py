@@ -51,6 +51,23 @@ def measure_profile(enc, pixels, tiles_per_image: int, tokens_per_tile: int, bat
     return points
 
 
+def save_profile(path: str, profile: Sequence[ProfilePoint], meta: dict | None = None) -> None:
+    """Write a measured profile as JSON so that it can be cached and shared between instances of the same
+    encoder and device type (Sec. 4.1: profiles are generated offline and reused)."""
+    import json
+
+    with open(path, "w") as f:
+        json.dump({"meta": meta or {}, "points": [[p.images, p.tokens, p.latency_ms] for p in _check(profile)]}, f)
+
+
+def load_profile(path: str) -> List[ProfilePoint]:
+    import json
+
+    with open(path) as f:
+        doc = json.load(f)
+    return _check([ProfilePoint(int(i), int(t), float(ms)) for i, t, ms in doc["points"]])
+
+
 def _check(profile: Sequence[ProfilePoint]) -> List[ProfilePoint]:
     pts = sorted(profile, key=lambda p: p.images)
     if not pts:

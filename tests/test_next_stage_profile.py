@@ -4,6 +4,7 @@ import math
 
 import pytest
 
+from paper_2502_00937_amd import stage_profile as SP
 from paper_2502_00937_amd.stage_profile import (ProfilePoint, capacity_tokens_per_s, latency_at,
                                                 max_batch_under_slo, replicas)
 
@@ -51,3 +52,12 @@ def test_bad_profiles_are_rejected():
     with pytest.raises(ValueError):
         latency_at([ProfilePoint(4, 4, 1.0), ProfilePoint(4, 4, 2.0)], 1)
     assert latency_at([ProfilePoint(4, 4, 2.0)], 8) == 4.0  # one point: proportional
+
+
+def test_profile_round_trips_through_a_file(tmp_path):
+    prof = [SP.ProfilePoint(8, 4616, 5.6), SP.ProfilePoint(1, 577, 2.8), SP.ProfilePoint(64, 36928, 30.3)]
+    path = tmp_path / "profile.json"
+    SP.save_profile(str(path), prof, meta={"encoder": "test", "device": "none"})
+    back = SP.load_profile(str(path))
+    assert back == sorted(prof, key=lambda p: p.images)
+    assert SP.max_batch_under_slo(back, 10.0) == SP.max_batch_under_slo(prof, 10.0)
