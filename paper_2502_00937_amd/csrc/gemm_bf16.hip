@@ -288,7 +288,10 @@ __device__ __forceinline__ void wave_epilogue_p(const GemmArgs& a, f32x16 (&acc)
           const int sr = p * 8 + (lane >> 3);
           const u32x4 t = *(const u32x4*)(st + sr * D_STAGING_ROW + sc * 2);
           if (i * 32 + half * 16 + p * 8 < row_lim && col_ok)
-            *(u32x4*)(tile_base + (size_t)(i * 32 + half * 16 + p * 8) * a.ldo * 2 + lane_off) = t;
+            // non-temporal: the 1 GB outputs of these products pass through L2 once; keeping them out of
+            // it leaves the operands there (-1 % on the encode step; whole 128-byte row pieces only: the
+            // same hint on the attention kernel's 8-byte stores cost 10 %)
+            __builtin_nontemporal_store(t, (u32x4*)(tile_base + (size_t)(i * 32 + half * 16 + p * 8) * a.ldo * 2 + lane_off));
         }
         __builtin_amdgcn_wave_barrier();
       }
