@@ -33,7 +33,7 @@ __global__ __launch_bounds__(256) void layernorm_kernel(const float* __restrict_
   for (int i = 0; i < MAXV; ++i) {
     const int c = (i * 64 + lane) * 4;
     if (c < D) {
-      v[i] = *(const f32x4*)(xr + c);
+      v[i] = __builtin_nontemporal_load((const f32x4*)(xr + c));  // read once here: keep it from displacing operands (-1 % on the step)
       s += (v[i][0] + v[i][1]) + (v[i][2] + v[i][3]);
     } else {
       v[i] = f32x4{0.f, 0.f, 0.f, 0.f};
