@@ -100,6 +100,7 @@ struct GemmArgs {
   int cls;            // EPI_PATCH: 1 if a CLS row precedes the patches
   int epilogue;
   int reverse;        // 1: walk the row blocks from the last to the first (see vit_encode_packed)
+  int stream_out;     // 1: the bf16 output exceeds the memory-side cache; the persistent kernel stores it non-temporally
 };
 
 // Applies one epilogue to a single accumulator; the caller guarantees row < M and col < N.
@@ -149,7 +150,7 @@ hipError_t launch_attention_f32(const AttnArgs& a, hipStream_t s);
 // shared, templated on activation type inside
 hipError_t launch_layernorm(const float* x, int ldx, void* out, int ldo, int out_cols, const float* gamma,
                             const float* beta, float eps, int rows, int D, int normalize, int out_bf16, int reverse,
-                            hipStream_t s);
+                            int stream_in, hipStream_t s);  // stream_in: x exceeds the memory-side cache, read it non-temporally
 hipError_t launch_patch_gather(const float* pixels, void* patches, int ld, int n_tiles, int C, int S, int p, int g,
                                int Kpad, int out_bf16, hipStream_t s);
 hipError_t launch_cls_rows(float* x, int ldx, const float* cls, const float* pos, int n_tiles, int T, int D,

@@ -173,7 +173,7 @@ typedef __attribute__((address_space(3))) void* lptr_t;
 
 // Epilogue of one wave of the persistent kernel: same register layout as wave_epilogue, but staged
 // 16 rows at a time through the wave's private 16 x 144-byte LDS rows (`st`).
-template <int EPI>
+template <int EPI, bool STREAM_OUT>
 __device__ __forceinline__ void wave_epilogue_p(const GemmArgs& a, f32x16 (&acc)[4][2], const f32x4 (&bias)[2][4],
                                                 unsigned char* st, int row0, int ncol0, int lane) {
   constexpr int FM = 4, FN = 2;
@@ -287,11 +287,17 @@ __device__ __forceinline__ void wave_epilogue_p(const GemmArgs& a, f32x16 (&acc)
         for (int p = 0; p < 2; ++p) {  // 8 lanes per row (8 bf16 each), 8 rows per pass
           const int sr = p * 8 + (lane >> 3);
           const u32x4 t = *(const u32x4*)(st + sr * D_STAGING_ROW + sc * 2);
-          if (i * 32 + half * 16 + p * 8 < row_lim && col_ok)
-            // non-temporal: the 1 GB outputs of these products pass through L2 once; keeping them out of
-            // it leaves the operands there (-1 % on the encode step; whole 128-byte row pieces only: the
-            // same hint on the attention kernel's 8-byte stores cost 10 %)
-            __builtin_nontemporal_store(t, (u32x4*)(tile_base + (size_t)(i * 32 + half * 16 + p * 8) * a.ldo * 2 + lane_off));
+          if (i * 32 + half * 16 + p * 8 < row_lim && col_ok) {
+            u32x4* dst = (u32x4*)(tile_base + (size_t)(i * 32 + half * 16 + p * 8) * a.ldo * 2 + lane_off);
+            // STREAM_OUT: the output is larger than the memory-side cache; it passes through once and
+            // would only displace the operands, so it is stored non-temporally (-1 % on the large encode
+            // step).  Smaller outputs are what the next kernel finds in that cache; there the hint costs
+            // 2-5 %.  (A compile-time flag: a run-time choice between the two stores gets merged into one
+            // plain store.)  Whole 128-byte row pieces only: on the attention kernel's 8-byte stores the
+            // hint cost 10 %.
+            if constexpr (STREAM_OUT) __builtin_nontemporal_store(t, dst);
+            else *dst = t;
+          }
         }
         __builtin_amdgcn_wave_barrier();
       }
@@ -299,7 +305,7 @@ __device__ __forceinline__ void wave_epilogue_p(const GemmArgs& a, f32x16 (&acc)
   }
 }
 
-template <int EPI>
+template <int EPI, bool STREAM_OUT>
 __global__ __launch_bounds__(512) void gemm_bf16_dma_kernel(const GemmArgs a, int tiles_m, int tiles_n, int n_bands,
                                                             int groups_full, int narrow_w, int n_groups) {
   constexpr int FM = 4, FN = 2, TM = 128, TN = 64;
@@ -510,7 +516,7 @@ __global__ __launch_bounds__(512) void gemm_bf16_dma_kernel(const GemmArgs a, in
     for (int j = 0; j < FN; ++j)
 #pragma unroll
       for (int jj = 0; jj < 4; ++jj) bias[j][jj] = *(const f32x4*)(a.bias + ncol0 + j * 32 + jj * 8 + lk * 4);
-    wave_epilogue_p<EPI>(a, acc, bias, staging + wave * 16 * D_STAGING_ROW, row0, ncol0, lane);
+    wave_epilogue_p<EPI, STREAM_OUT>(a, acc, bias, staging + wave * 16 * D_STAGING_ROW, row0, ncol0, lane);
   }
 }
 
@@ -684,9 +690,9 @@ hipError_t launch_dma(const GemmArgs& a, hipStream_t s) {
   // one workgroup per compute unit: 8 XCDs x 32 slots (slots beyond the unit count of an XCD stay off)
   const int grid = 8 * D_GROUP_M * D_GROUP_N;
   if (n_cu < grid) return hipErrorInvalidValue;
-#define VIT_LAUNCH(EPI)                                                                                              \
+#define VIT_LAUNCH(EPI, STREAM)                                                                                      \
   do {                                                                                                               \
-    auto kfn = gemm_bf16_dma_kernel<EPI>;                                                                            \
+    auto kfn = gemm_bf16_dma_kernel<EPI, STREAM>;                                                                    \
     static bool attr_set = false;                                                                                    \
     if (!attr_set) {                                                                                                 \
       hipError_t e = hipFuncSetAttribute((const void*)kfn, hipFuncAttributeMaxDynamicSharedMemorySize, D_LDS_BYTES); \
@@ -697,10 +703,16 @@ hipError_t launch_dma(const GemmArgs& a, hipStream_t s) {
                        narrow_w, n_groups);                                                                          \
   } while (0)
   switch (a.epilogue) {
-    case EPI_BIAS: VIT_LAUNCH(EPI_BIAS); break;
-    case EPI_BIAS_GELU: VIT_LAUNCH(EPI_BIAS_GELU); break;
-    case EPI_BIAS_RESIDUAL: VIT_LAUNCH(EPI_BIAS_RESIDUAL); break;
-    case EPI_PATCH: VIT_LAUNCH(EPI_PATCH); break;
+    case EPI_BIAS:
+      if (a.stream_out) VIT_LAUNCH(EPI_BIAS, true);
+      else VIT_LAUNCH(EPI_BIAS, false);
+      break;
+    case EPI_BIAS_GELU:
+      if (a.stream_out) VIT_LAUNCH(EPI_BIAS_GELU, true);
+      else VIT_LAUNCH(EPI_BIAS_GELU, false);
+      break;
+    case EPI_BIAS_RESIDUAL: VIT_LAUNCH(EPI_BIAS_RESIDUAL, false); break;
+    case EPI_PATCH: VIT_LAUNCH(EPI_PATCH, false); break;
     default: return hipErrorInvalidValue;
   }
 #undef VIT_LAUNCH

@@ -17,7 +17,7 @@ __device__ inline float wave_sum(float v) {
 // centred values (no E[x^2] - mean^2 cancellation).  Columns D..out_cols-1 of the output
 // are written as zero so the row can feed a K-padded matrix product.
 // NORMALIZE = 0 turns the kernel into a plain fp32 -> OutT conversion.
-template <typename OutT, int MAXV, int NORMALIZE>
+template <typename OutT, int MAXV, int NORMALIZE, bool STREAM_IN>
 __global__ __launch_bounds__(256) void layernorm_kernel(const float* __restrict__ x, int ldx, OutT* __restrict__ out,
                                                         int ldo, int out_cols, const float* __restrict__ gamma,
                                                         const float* __restrict__ beta, float eps, int rows, int D,
@@ -33,7 +33,11 @@ __global__ __launch_bounds__(256) void layernorm_kernel(const float* __restrict_
   for (int i = 0; i < MAXV; ++i) {
     const int c = (i * 64 + lane) * 4;
     if (c < D) {
-      v[i] = __builtin_nontemporal_load((const f32x4*)(xr + c));  // read once here: keep it from displacing operands (-1 % on the step)
+      // STREAM_IN: x is larger than the memory-side cache; it is read once here and non-temporally, so that
+      // it does not displace operands (-1 % on the large encode step).  A small x sits in L2, where the hint
+      // costs 2-5 %.  (Compile-time: a run-time choice between the two loads gets merged into one plain load.)
+      if constexpr (STREAM_IN) v[i] = __builtin_nontemporal_load((const f32x4*)(xr + c));
+      else v[i] = *(const f32x4*)(xr + c);
       s += (v[i][0] + v[i][1]) + (v[i][2] + v[i][3]);
     } else {
       v[i] = f32x4{0.f, 0.f, 0.f, 0.f};
@@ -145,12 +149,17 @@ __global__ __launch_bounds__(256) void token_merge_kernel(const unsigned char* _
 
 template <typename OutT, int NORMALIZE>
 hipError_t ln_dispatch(const float* x, int ldx, void* out, int ldo, int out_cols, const float* gamma, const float* beta,
-                       float eps, int rows, int D, int reverse, hipStream_t s) {
+                       float eps, int rows, int D, int reverse, int stream_in, hipStream_t s) {
   const dim3 grid((rows + 3) / 4), block(256);
   const int need = (out_cols + 255) / 256;  // float4 slots per lane
-#define VIT_LN(MAXV)                                                                                              \
-  hipLaunchKernelGGL((layernorm_kernel<OutT, MAXV, NORMALIZE>), grid, block, 0, s, x, ldx, (OutT*)out, ldo, out_cols, \
-                     gamma, beta, eps, rows, D, reverse)
+#define VIT_LN_S(MAXV, STREAM)                                                                                    \
+  hipLaunchKernelGGL((layernorm_kernel<OutT, MAXV, NORMALIZE, STREAM>), grid, block, 0, s, x, ldx, (OutT*)out, ldo, \
+                     out_cols, gamma, beta, eps, rows, D, reverse)
+#define VIT_LN(MAXV)                        \
+  do {                                      \
+    if (stream_in) VIT_LN_S(MAXV, true);    \
+    else VIT_LN_S(MAXV, false);             \
+  } while (0)
   if (need <= 1) VIT_LN(1);
   else if (need <= 2) VIT_LN(2);
   else if (need <= 4) VIT_LN(4);
@@ -159,6 +168,7 @@ hipError_t ln_dispatch(const float* x, int ldx, void* out, int ldo, int out_cols
   else if (need <= 16) VIT_LN(16);
   else return hipErrorInvalidValue;
 #undef VIT_LN
+#undef VIT_LN_S
   return hipGetLastError();
 }
 
@@ -166,15 +176,15 @@ hipError_t ln_dispatch(const float* x, int ldx, void* out, int ldo, int out_cols
 
 hipError_t launch_layernorm(const float* x, int ldx, void* out, int ldo, int out_cols, const float* gamma,
                             const float* beta, float eps, int rows, int D, int normalize, int out_bf16, int reverse,
-                            hipStream_t s) {
+                            int stream_in, hipStream_t s) {
   if (rows <= 0) return hipSuccess;
   if (D % 4 != 0 || out_cols % 4 != 0 || ldx % 4 != 0 || ldo % 4 != 0 || out_cols < D) return hipErrorInvalidValue;
   if (out_bf16) {
-    return normalize ? ln_dispatch<bf16_t, 1>(x, ldx, out, ldo, out_cols, gamma, beta, eps, rows, D, reverse, s)
-                     : ln_dispatch<bf16_t, 0>(x, ldx, out, ldo, out_cols, gamma, beta, eps, rows, D, reverse, s);
+    return normalize ? ln_dispatch<bf16_t, 1>(x, ldx, out, ldo, out_cols, gamma, beta, eps, rows, D, reverse, stream_in, s)
+                     : ln_dispatch<bf16_t, 0>(x, ldx, out, ldo, out_cols, gamma, beta, eps, rows, D, reverse, stream_in, s);
   }
-  return normalize ? ln_dispatch<float, 1>(x, ldx, out, ldo, out_cols, gamma, beta, eps, rows, D, reverse, s)
-                   : ln_dispatch<float, 0>(x, ldx, out, ldo, out_cols, gamma, beta, eps, rows, D, reverse, s);
+  return normalize ? ln_dispatch<float, 1>(x, ldx, out, ldo, out_cols, gamma, beta, eps, rows, D, reverse, stream_in, s)
+                   : ln_dispatch<float, 0>(x, ldx, out, ldo, out_cols, gamma, beta, eps, rows, D, reverse, stream_in, s);
 }
 
 hipError_t launch_patch_gather(const float* pixels, void* patches, int ld, int n_tiles, int C, int S, int p, int g,

@@ -546,6 +546,9 @@ vit_status_t vit_encode_packed(vit_encoder_t* e, const float* pixels, const int3
     slot.used = true;
   }
 
+  // Streams larger than the 256 MB memory-side cache get non-temporal hints: they cannot be found there by
+  // the next kernel anyway and would only displace operands; smaller ones are left to the caches.
+  constexpr size_t kCacheBytes = (size_t)256 << 20;
   // Every kernel of the chain walks the token rows in the direction opposite to its producer:
   // what a kernel wrote last is still in the 256 MB memory-side cache when its consumer starts there.
   int reverse = 0;
@@ -557,6 +560,7 @@ vit_status_t vit_encode_packed(vit_encoder_t* e, const float* pixels, const int3
     a.patches = d.P; a.tokens = d.T; a.cls = d.has_cls; a.epilogue = epi;
     a.reverse = reverse;
     reverse ^= 1;
+    a.stream_out = (size_t)M * lin.N * d.es > kCacheBytes;
     ProfScope ps(e, s, VIT_PROF_GEMM);
     return d.bf16 ? launch_gemm_bf16(a, s) : launch_gemm_f32(a, s);
   };
@@ -564,7 +568,8 @@ vit_status_t vit_encode_packed(vit_encoder_t* e, const float* pixels, const int3
     ProfScope ps(e, s, VIT_PROF_LAYERNORM);
     const int rev = reverse;
     reverse ^= 1;
-    return launch_layernorm(x, d.D, out, ldo, out_cols, g_, b_, d.eps, n_tok, d.D, normalize, d.bf16, rev, s);
+    return launch_layernorm(x, d.D, out, ldo, out_cols, g_, b_, d.eps, n_tok, d.D, normalize, d.bf16, rev,
+                            (size_t)n_tok * d.D * 4 > kCacheBytes, s);
   };
 
   // ---- patch embedding: gather -> matrix product with (+bias, +pos, row remap) epilogue; CLS rows
