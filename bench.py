@@ -140,6 +140,34 @@ def sweep(args, torch, gen, V):
                                                     "p99": float(np.percentile(r, 99)), "max": float(r.max())}}))
 
 
+def vendor_gemm(torch, gen):
+    """The vendor library's plain bf16 product C = A W^T (no bias, no epilogue) on the matrix-product shapes of
+    one config-3 step, random operands.  Context for `roofline`: what the library reaches on this device for the
+    same contraction, without the fused epilogues the encoder's kernels carry.  Not part of the encode path."""
+    cfg, ipr, to = gen.make_workload("cfg3")
+    m = int(to[-1]) * gen.tokens_per_tile(cfg)
+    D, M = cfg["hidden"], cfg["mlp"]
+    shapes = [("qkv", 3 * D, D), ("out-proj", D, D), ("fc1", M, D), ("fc2", D, M),
+              ("projector 2", cfg["proj_dims"][1], cfg["proj_dims"][0])]
+    g = torch.Generator(device="cuda").manual_seed(0)
+    for name, n, k in shapes:
+        a = (torch.rand((m, k), device="cuda", generator=g) * 2 - 1).to(torch.bfloat16)
+        w = ((torch.rand((n, k), device="cuda", generator=g) * 2 - 1) * 0.02).to(torch.bfloat16)
+        for _ in range(3):
+            c = a @ w.t()
+        ev = [torch.cuda.Event(enable_timing=True) for _ in range(2)]
+        torch.cuda.synchronize()
+        reps = 20
+        ev[0].record()
+        for _ in range(reps):
+            c = a @ w.t()
+        ev[1].record()
+        torch.cuda.synchronize()
+        ms = ev[0].elapsed_time(ev[1]) / reps
+        print(json.dumps({"vendor_gemm": name, "M": m, "N": n, "K": k, "ms": ms, "tflops": 2.0 * m * n * k / ms / 1e9}))
+        del a, w, c
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -151,6 +179,8 @@ def main():
     ap.add_argument("--sweep", action="store_true",
                     help="instead of the benchmark line: encode 1, 8, 64 and 260 images of the config-3 model (one JSON "
                          "line per size) and config 3 repacked as 260 single-image requests / one 260-image request")
+    ap.add_argument("--vendor-gemm", action="store_true",
+                    help="time the vendor library's bf16 matrix product (torch.matmul) on the step's shapes: context only")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="run five plain 1 GiB device copies and exit (scale reference for rocprofv3 FETCH_SIZE / WRITE_SIZE)")
     args = ap.parse_args()
@@ -173,6 +203,9 @@ def main():
             dst.copy_(src)
         torch.cuda.synchronize()
         print(json.dumps({"copy_calibration": {"bytes_read": 1 << 30, "bytes_written": 1 << 30, "copies": 5}}))
+        return
+    if args.vendor_gemm:
+        vendor_gemm(torch, gen)
         return
     if args.sweep:
         sweep(args, torch, gen, V)
