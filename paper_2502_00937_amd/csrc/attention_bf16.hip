@@ -324,12 +324,8 @@ hipError_t launch_attention_bf16(const AttnArgs& a, hipStream_t s) {
   do {                                                                                                 \
     constexpr int smem = 2 * AttnShape<DHP, QB, NW>::STAGE;                                            \
     auto kfn = attention_bf16_kernel<DHP, QB, NW>;                                                     \
-    static bool attr_set = false; /* the dynamic LDS limit is raised once per kernel */                \
-    if (!attr_set) {                                                                                   \
-      hipError_t e = hipFuncSetAttribute((const void*)kfn, hipFuncAttributeMaxDynamicSharedMemorySize, smem); \
-      if (e != hipSuccess) return e;                                                                   \
-      attr_set = true;                                                                                 \
-    }                                                                                                  \
+    static LdsLimitOnce lds_limit; /* raised once per kernel and device */                             \
+    if (hipError_t e = lds_limit.ensure((const void*)kfn, smem); e != hipSuccess) return e;            \
     hipLaunchKernelGGL(kfn, grid, dim3(AttnShape<DHP, QB, NW>::ANT), smem, s, a, scale_log2);          \
   } while (0)
   switch (a.dh_pad) {

@@ -642,12 +642,8 @@ hipError_t launch_ring(const GemmArgs& a, hipStream_t s) {
   do {                                                                                                               \
     auto kfn = gemm_bf16_ring_kernel<EPI, NS>;                                                                       \
     constexpr int lds = NS * R_STAGE_BYTES;                                                                          \
-    static bool attr_set = false;                                                                                    \
-    if (!attr_set) {                                                                                                 \
-      hipError_t e = hipFuncSetAttribute((const void*)kfn, hipFuncAttributeMaxDynamicSharedMemorySize, lds);         \
-      if (e != hipSuccess) return e;                                                                                 \
-      attr_set = true;                                                                                               \
-    }                                                                                                                \
+    static LdsLimitOnce lds_limit;                                                                                   \
+    if (hipError_t e = lds_limit.ensure((const void*)kfn, lds); e != hipSuccess) return e;                           \
     hipLaunchKernelGGL(kfn, dim3((unsigned)grid), dim3(512), lds, s, a, tiles_m, tiles_n, mt_per_xcd, n_bands);      \
   } while (0)
 #define VIT_LAUNCH(EPI)           \
@@ -679,13 +675,15 @@ hipError_t launch_dma(const GemmArgs& a, hipStream_t s) {
   const int groups_full = ((tiles_m + D_GROUP_M - 1) / D_GROUP_M) * n_bands;
   const int groups_narrow = narrow_w ? (tiles_m + 32 / narrow_w - 1) / (32 / narrow_w) : 0;
   const int n_groups = groups_full + groups_narrow;
-  static int n_cu = 0;
+  // compute units of the current device, looked up once per device
+  static std::atomic<int> cu_of_device[64];
+  int dev = 0;
+  if (hipError_t e = hipGetDevice(&dev); e != hipSuccess) return e;
+  if (dev < 0 || dev >= 64) return hipErrorInvalidDevice;
+  int n_cu = cu_of_device[dev].load(std::memory_order_relaxed);
   if (n_cu == 0) {
-    int dev = 0;
-    hipError_t e = hipGetDevice(&dev);
-    if (e != hipSuccess) return e;
-    e = hipDeviceGetAttribute(&n_cu, hipDeviceAttributeMultiprocessorCount, dev);
-    if (e != hipSuccess) return e;
+    if (hipError_t e = hipDeviceGetAttribute(&n_cu, hipDeviceAttributeMultiprocessorCount, dev); e != hipSuccess) return e;
+    cu_of_device[dev].store(n_cu, std::memory_order_relaxed);
   }
   // one workgroup per compute unit: 8 XCDs x 32 slots (slots beyond the unit count of an XCD stay off)
   const int grid = 8 * D_GROUP_M * D_GROUP_N;
@@ -693,12 +691,8 @@ hipError_t launch_dma(const GemmArgs& a, hipStream_t s) {
 #define VIT_LAUNCH(EPI, STREAM)                                                                                      \
   do {                                                                                                               \
     auto kfn = gemm_bf16_dma_kernel<EPI, STREAM>;                                                                    \
-    static bool attr_set = false;                                                                                    \
-    if (!attr_set) {                                                                                                 \
-      hipError_t e = hipFuncSetAttribute((const void*)kfn, hipFuncAttributeMaxDynamicSharedMemorySize, D_LDS_BYTES); \
-      if (e != hipSuccess) return e;                                                                                 \
-      attr_set = true;                                                                                               \
-    }                                                                                                                \
+    static LdsLimitOnce lds_limit;                                                                                   \
+    if (hipError_t e = lds_limit.ensure((const void*)kfn, D_LDS_BYTES); e != hipSuccess) return e;                   \
     hipLaunchKernelGGL(kfn, dim3(grid), dim3(512), D_LDS_BYTES, s, a, tiles_m, tiles_n, n_bands, groups_full,        \
                        narrow_w, n_groups);                                                                          \
   } while (0)

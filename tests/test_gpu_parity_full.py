@@ -35,9 +35,12 @@ def test_cfg2_vitl14_336_full():
 
 def test_cfg3_ragged_batch_sampled():
     cfg, ipr, tpi = _workload("cfg3")
-    # first, last, one inside the 32-image request (request 47), one single-image request
+    # first, last, three inside the 32-image request (request 47: its first, one inside, its last), one of
+    # the 26-image request, two single-image requests
     first_of_req = np.concatenate([[0], np.cumsum(ipr)])
-    images = [0, int(first_of_req[47]) + 17, int(first_of_req[60]), 259]
+    assert ipr[47] == 32 and ipr[48] == 26 and ipr[60] == 1 and ipr[9] == 1
+    r47 = int(first_of_req[47])
+    images = [0, int(first_of_req[9]), r47, r47 + 17, r47 + 31, int(first_of_req[48]) + 12, int(first_of_req[60]), 259]
     say(f"case cfg3 (260 images / 64 requests), oracle on images {images}")
     got, _ = check_case(cfg, tpi, ipr, images=images, label="cfg3")
     assert got.shape == (260 * 577, 4096)
@@ -45,8 +48,8 @@ def test_cfg3_ragged_batch_sampled():
 
 def test_cfg4_siglip_tiles_sampled():
     cfg, ipr, tpi = _workload("cfg4")
-    images = [5, 127]          # a 2-tile image and the last image (5 tiles)
-    assert tpi[5] == 2
+    images = [0, 5, 64, 127]   # the first image (7 tiles, the maximum), a 2-tile one, one inside, the last (5 tiles)
+    assert tpi[0] == 7 and tpi[5] == 2 and tpi[127] == 5
     say(f"case cfg4 (128 images / 591 tiles), oracle on images {images}")
     got, _ = check_case(cfg, tpi, ipr, images=images, oracle_dtype=np.float32, label="cfg4")
     assert got.shape == (591 * 729, 4096)
