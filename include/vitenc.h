@@ -105,7 +105,8 @@ vit_status_t vit_encoder_query(const vit_encoder_t* enc, int32_t n_tiles, int32_
 /*
  * Encode one packed batch (patchify + position add, all blocks, final LN, projector).
  *   pixels              DEVICE, [n_tiles, C, S, S] fp32, already normalised (preprocessing
- *                       is the CPU stage before this one, paper Sec. 2).
+ *                       is the stage before this one, paper Sec. 2; vit_preprocess_tiles
+ *                       below writes this layout).
  *   images_per_request  HOST, [n_requests], each >= 0 (0 = text-only request, which owns
  *                       an empty token range); sum = n_images.
  *   tile_offsets        HOST, [n_images + 1], prefix sum of tiles per image:
