@@ -73,3 +73,32 @@ def test_cfg6_6b_downsampled_sampled():
     say(f"case cfg6 (8 images / 36 tiles, 6B-class, 2x2 down-sampling), oracle on image {images}")
     got, _ = check_case(cfg, tpi, ipr, images=images, oracle_dtype=np.float32, label="cfg6")
     assert got.shape == (36 * 256, 6144)
+
+
+def test_tokens_are_bit_identical_at_every_batch_size():
+    """An image's tokens do not depend on how many images share its launch: 1, 2 and 8 images run every
+    product on the 128 x 128 ring kernel (four- and two-stage rings), 64 images mix both matrix-product
+    kernels, 260 images run the persistent 256 x 256 kernel, and all of them add a token's k-steps in the
+    same order.  Compared bit for bit against the full config-3 batch."""
+    import torch
+
+    import paper_2502_00937_amd as V
+
+    cfg, ipr, tpi = _workload("cfg3")
+    say("case batch-size invariance (config-3 model: 260, 64, 8, 2, 1 images)")
+    enc = V.VitEncoder(cfg, gen.make_weights(cfg, seed=0), device=0)
+    px = torch.from_numpy(gen.make_pixels(cfg, 260, seed=1)).cuda()
+    T = gen.tokens_per_tile(cfg)
+    full, _ = enc.encode(px, ipr, np.arange(261, dtype=np.int32))
+    torch.cuda.synchronize()
+    for n in (64, 8, 2, 1):
+        part, _ = enc.encode(px[:n], [n], np.arange(n + 1, dtype=np.int32))
+        torch.cuda.synchronize()
+        same = torch.equal(part.view(torch.int16), full[:n * T].view(torch.int16))
+        say(f"    {n} images against the first {n} of 260: bit-identical = {same}")
+        assert same, n
+    # images from the far end of the batch, encoded alone
+    tail, _ = enc.encode(px[257:], [3], np.arange(4, dtype=np.int32))
+    torch.cuda.synchronize()
+    assert torch.equal(tail.view(torch.int16), full[257 * T:].view(torch.int16))
+    enc.close()
