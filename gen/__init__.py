@@ -4,7 +4,14 @@ This module serves both the CPU oracle's tests and the HIP library's tests and
 benchmark.  It produces *inputs only* (encoder shapes, weights, pixels, request
 structure); it contains none of the encoder's arithmetic.
 """
-from .configs import CONFIGS, get_config, out_tokens_per_tile, tokens_per_tile, weight_count  # noqa: F401
+from .configs import (  # noqa: F401
+    CONFIGS,
+    get_config,
+    out_tokens_per_tile,
+    tokens_per_tile,
+    weight_count,
+    weight_layout,
+)
 from .inputs import (  # noqa: F401
     CFG3_IMAGES_PER_REQUEST,
     CFG4_TILES_PER_IMAGE,

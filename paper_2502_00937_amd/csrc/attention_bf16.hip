@@ -19,8 +19,8 @@
 // hardware interleaves their dependency chains; the logit scale is folded into the exp2 argument
 // (one fma per element); full key tiles carry no mask code at all (a segment's last tile is a
 // separate instantiation that also skips an empty key half, and waves with no valid query row skip
-// the arithmetic); the output accumulator is rescaled only when some lane's logits outgrow the
-// reference maximum by 2^8.
+// the arithmetic); the row maximum is not computed on the common path: the reference maximum moves, and
+// the output accumulator is rescaled, only when a row sum of exponentials reaches 2^64.
 // K/V tiles of 64 keys are double-buffered in LDS: the next tile's global loads are issued before
 // the current tile is processed and written to the other buffer afterwards (one barrier per tile).
 #include <type_traits>
@@ -32,7 +32,7 @@ namespace vitenc {
 namespace {
 
 constexpr int AKV = 64;  // keys per LDS tile
-constexpr float RESCALE_SLACK = 8.0f;  // log2 units the logits may exceed the reference maximum by
+constexpr float REFERENCE_LIMIT = 18446744073709551616.0f;  // 2^64: a row sum this large moves the reference maximum
 
 // QB = 32-query blocks per wave, NW = waves per workgroup: a work item is 32 * QB * NW query rows.
 // All head dims run QB = 1, NW = 4 (128 rows); QB = 2 (each K / V^T fragment feeding two MFMAs, two
@@ -197,8 +197,18 @@ __global__ __launch_bounds__(64 * NW, QB == 1 ? (DHP == 64 ? 4 : DHP <= 96 ? 3 :
     for (int kb = 0; kb < 2; ++kb) {
       if (!wave_active) break;  // (the wave still stages K / V and meets the barriers)
       if (MASK && kb * 32 >= remaining) break;  // the second half of the last tile may hold no key at all
-      // ---- S^T = K . Q^T: each K fragment feeds all query blocks of the wave
+      // ---- S^T = K . Q^T: each K fragment feeds all query blocks of the wave; keys past the segment end are
+      //      masked (only a segment's last tile has any)
       f32x16 st[QB];
+      auto mask = [&](f32x16& sq) {
+        if (MASK) {
+#pragma unroll
+          for (int v = 0; v < 16; ++v) {
+            const int key = kb * 32 + 8 * (v >> 2) + 4 * g + (v & 3);
+            if (key >= remaining) sq[v] = -INFINITY;
+          }
+        }
+      };
 #pragma unroll
       for (int qb = 0; qb < QB; ++qb)
 #pragma unroll
@@ -210,30 +220,44 @@ __global__ __launch_bounds__(64 * NW, QB == 1 ? (DHP == 64 ? 4 : DHP <= 96 ? 3 :
         for (int qb = 0; qb < QB; ++qb)
           st[qb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[qb][ks], st[qb], 0, 0, 0);
       }
-      // ---- mask keys past the segment end (only a segment's last tile has any)
-      if (MASK) {
 #pragma unroll
-        for (int qb = 0; qb < QB; ++qb)
-#pragma unroll
-          for (int v = 0; v < 16; ++v) {
-            const int key = kb * 32 + 8 * (v >> 2) + 4 * g + (v & 3);
-            if (key >= remaining) st[qb][v] = -INFINITY;
-          }
-      }
+      for (int qb = 0; qb < QB; ++qb) mask(st[qb]);
       // ---- online softmax per query block; P^T replaces S^T as bf16 fragments
       bf16x8 pf[QB][2];
 #pragma unroll
       for (int qb = 0; qb < QB; ++qb) {
-        float mx = st[qb][0];
+        // P^T = exp2(S^T * scale - m) with the reference maximum m as it stands.  m only has to keep exp2
+        // in range, not to be the exact running maximum: P is a bf16 value and the sums are fp32, both with
+        // eight exponent bits, so logits may exceed m by 2^6 log2 units before anything is lost.  The row
+        // maximum is therefore not computed at all on the common path; a row sum that reaches 2^64 (or is
+        // not a number: m = -inf before the first tile) says that m has to move.
+        float psum;
+        auto exponentials = [&](const f32x16& sq, float neg_m) {
+          psum = 0.f;
 #pragma unroll
-        for (int v = 1; v < 16; ++v) mx = fmaxf(mx, st[qb][v]);
-        mx = fmaxf(mx, __builtin_bit_cast(float, __builtin_amdgcn_ds_bpermute(partner_addr, __builtin_bit_cast(int, mx))));
-        // The reference maximum m only has to keep exp2 in range, not to be the exact running
-        // maximum: it moves (and the accumulators are rescaled) only when some query's logits
-        // outgrow it by more than 2^RESCALE_SLACK, so p <= 2^RESCALE_SLACK instead of p <= 1.
-        const float m_new = mx * scale_log2;
-        if (__builtin_amdgcn_ballot_w64(m_new > m[qb] + RESCALE_SLACK) != 0) {
-          const float m_up = fmaxf(m[qb], m_new);
+          for (int s2 = 0; s2 < 2; ++s2) {
+            float p[8];
+#pragma unroll
+            for (int e = 0; e < 8; ++e) {
+              p[e] = __builtin_amdgcn_exp2f(fmaf(sq[s2 * 8 + e], scale_log2, neg_m));
+              psum += p[e];
+            }
+            const u32x4 pk = {pack_bf16x2(p[0], p[1]), pack_bf16x2(p[2], p[3]), pack_bf16x2(p[4], p[5]),
+                              pack_bf16x2(p[6], p[7])};
+            pf[qb][s2] = __builtin_bit_cast(bf16x8, pk);
+          }
+        };
+        exponentials(st[qb], -m[qb]);
+        if (__builtin_amdgcn_ballot_w64(!(psum < REFERENCE_LIMIT)) != 0) {
+          // Rare: move m to the maximum seen so far (the same for the two lanes that share a query), rescale
+          // the accumulators and redo the exponentials.  (Forming the logits again here instead of keeping
+          // them alive costs head dims 80 and 96 seven per cent: measured.)
+          const f32x16& sr = st[qb];
+          float mx = sr[0];
+#pragma unroll
+          for (int v = 1; v < 16; ++v) mx = fmaxf(mx, sr[v]);
+          mx = fmaxf(mx, __builtin_bit_cast(float, __builtin_amdgcn_ds_bpermute(partner_addr, __builtin_bit_cast(int, mx))));
+          const float m_up = fmaxf(m[qb], mx * scale_log2);
           const float corr = __builtin_amdgcn_exp2f(m[qb] - m_up);
           l[qb] *= corr;
 #pragma unroll
@@ -241,20 +265,7 @@ __global__ __launch_bounds__(64 * NW, QB == 1 ? (DHP == 64 ? 4 : DHP <= 96 ? 3 :
 #pragma unroll
             for (int v = 0; v < 16; ++v) o[qb][b][v] *= corr;
           m[qb] = m_up;
-        }
-        const float neg_m = -m[qb];
-        float psum = 0.f;
-#pragma unroll
-        for (int s2 = 0; s2 < 2; ++s2) {
-          float p[8];
-#pragma unroll
-          for (int e = 0; e < 8; ++e) {
-            p[e] = __builtin_amdgcn_exp2f(fmaf(st[qb][s2 * 8 + e], scale_log2, neg_m));
-            psum += p[e];
-          }
-          const u32x4 pk = {pack_bf16x2(p[0], p[1]), pack_bf16x2(p[2], p[3]), pack_bf16x2(p[4], p[5]),
-                            pack_bf16x2(p[6], p[7])};
-          pf[qb][s2] = __builtin_bit_cast(bf16x8, pk);
+          exponentials(sr, -m[qb]);
         }
         l[qb] += psum;
       }

@@ -3,6 +3,7 @@ import numpy as np
 import pytest
 
 import gen
+from oracle import vit_oracle as O
 from parity_util import assert_parity, check_case, gpu_encode, say
 
 pytestmark = pytest.mark.gpu
@@ -403,3 +404,49 @@ def test_random_small_encoders_match_oracle(seed):
     cfg, tpi, ipr = _random_case(seed)
     say(f"case random {seed}: {cfg} tiles/image {tpi} images/request {ipr}")
     check_case(cfg, tpi, ipr, wseed=seed, pseed=seed + 50, label=f"random{seed}")
+
+
+def test_attention_logits_that_outgrow_the_reference_maximum():
+    """Logits that rise by far more than 2^64 (as exp2 arguments) from the first keys of a segment to its last:
+    every query is -64 e_0, key t carries 8 cos(pi t / 256) in channel 0 (a position table on a circle, which
+    LayerNorm maps to that), so the logit of key t is -64 cos(pi t / 256): -64 ... +64 over 257 keys = five key
+    tiles.  The softmax reference of the attention kernel has to move several times after the first tile and the
+    accumulated output has to be rescaled each time; a lost rescale would show as garbage, inf or NaN."""
+    cfg = {"image_size": 64, "patch_size": 4, "channels": 3, "hidden": 64, "heads": 1, "mlp": 64, "layers_local": 1,
+           "layers_global": 0, "has_cls": 1, "final_ln": 0, "ln_eps": 1e-6, "proj_layers": 0, "proj_dims": (),
+           "dtype": "bf16", "token_merge": 1}
+    T, D = gen.tokens_per_tile(cfg), 64
+    assert T == 257
+    w = gen.make_weights(cfg, seed=3).copy()
+    off = {}
+    o = 0
+    for name, shape in gen.weight_layout(cfg):
+        n = int(np.prod(shape))
+        off[name] = (o, shape)
+        o += n
+
+    def view(name):
+        a, shape = off[name]
+        return w[a:a + int(np.prod(shape))].reshape(shape)
+
+    theta = np.pi * np.arange(T) / (T - 1)
+    view("pos")[:, 0] = 4.0 * np.cos(theta)
+    view("pos")[:, 1] = 4.0 * np.sin(theta)
+    view("l0.ln1_g")[:] = 1.0
+    view("l0.ln1_b")[:] = 0.0
+    wqkv, bqkv = view("l0.wqkv"), view("l0.bqkv")
+    wqkv[:D] = 0.0
+    bqkv[:D] = 0.0
+    bqkv[0] = -64.0                       # q = -64 e_0 for every token
+    wqkv[D, :] = 0.0
+    wqkv[D, 0] = 1.0                      # k[0] = normalised channel 0 = 8 cos(theta)
+    bqkv[D] = 0.0
+    wqkv[2 * D:] *= 10.0                  # values and output projection large enough to matter beside x
+    view("l0.wo")[:] *= 10.0
+    w = gen.round_to_bf16(w)
+    px = gen.make_pixels(cfg, 3, seed=5)
+    to = np.array([0, 1, 3], dtype=np.int32)
+    say("case logits outgrowing the softmax reference (257 keys, logits -64 ... +64)")
+    got, _ = gpu_encode(cfg, w, px, [2], to)
+    want, _ = O.vit_oracle_encode(cfg, w, px, [2], to)
+    assert_parity(got, want, "bf16", "rising logits")
