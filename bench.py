@@ -140,6 +140,35 @@ def sweep(args, torch, gen, V):
                                                     "p99": float(np.percentile(r, 99)), "max": float(r.max())}}))
 
 
+def serve(torch, gen, V):
+    """One Image Instance run against the wall clock on a seeded heavy-tailed request stream (Sec. 4.2, 4.3): launches
+    of what has arrived, up to the maximum batch under a 50 ms SLO; the encode latency per request beside what
+    the event model of `router.simulate` predicts for one instance from the stage profile measured first."""
+    from paper_2502_00937_amd import router as R
+    from paper_2502_00937_amd import stage_profile as SP
+    from paper_2502_00937_amd.image_instance import ImageInstance, percentiles
+
+    cfg, _, _ = gen.make_workload("cfg3")
+    enc = V.VitEncoder(cfg, gen.make_weights(cfg, seed=0), device=0)
+    T = gen.tokens_per_tile(cfg)
+    px = torch.from_numpy(gen.make_pixels(cfg, 128, seed=1)).cuda()
+    profile = SP.measure_profile(enc, px, 1, T, (1, 2, 3, 4, 6, 8, 12, 16, 24, 32, 48, 64, 96, 128))
+    b50 = max(1, min(128, SP.max_batch_under_slo(profile, 50.0)))
+    lat = lambda images, tiles: SP.latency_at(profile, images)  # noqa: E731
+    inst = ImageInstance(enc, px, max_images=b50)
+    for gap in (8.0, 4.0, 2.5):  # mean inter-arrival time in ms; about 4 images per request
+        arrivals = gen.make_arrivals(1200, gap, seed=0)
+        measured, launches = inst.run_stream(arrivals)
+        model = R.simulate(arrivals, 1, T, lat, b50, "least_image_tokens")
+        keys = ("p50", "p90", "p99")
+        print(json.dumps({"serve": "one Image Instance, real time", "mean_interarrival_ms": gap, "requests": len(arrivals),
+                          "images": int(sum(len(t) for _, t in arrivals)), "max_images_per_launch": b50,
+                          "launches": len(launches), "mean_images_per_launch": float(np.mean([l[0] for l in launches])),
+                          "encode_latency_ms": dict(zip(keys, percentiles(measured)), max=float(max(measured))),
+                          "event_model_ms": dict(zip(keys, percentiles(model)), max=float(max(model)))}))
+    enc.close()
+
+
 def vendor_gemm(torch, gen):
     """The vendor library's plain bf16 product C = A W^T (no bias, no epilogue) on the matrix-product shapes of
     one config-3 step, random operands.  Context for `roofline`: what the library reaches on this device for the
@@ -179,6 +208,9 @@ def main():
     ap.add_argument("--sweep", action="store_true",
                     help="instead of the benchmark line: encode 1, 8, 64 and 260 images of the config-3 model (one JSON "
                          "line per size) and config 3 repacked as 260 single-image requests / one 260-image request")
+    ap.add_argument("--serve", action="store_true",
+                    help="run one Image Instance in real time on a seeded request stream (three arrival rates, about 20 s) "
+                         "and print measured encode latencies beside the event model's")
     ap.add_argument("--vendor-gemm", action="store_true",
                     help="time the vendor library's bf16 matrix product (torch.matmul) on the step's shapes: context only")
     ap.add_argument("--copy-calibration", action="store_true",
@@ -209,6 +241,9 @@ def main():
         return
     if args.sweep:
         sweep(args, torch, gen, V)
+        return
+    if args.serve:
+        serve(torch, gen, V)
         return
     cfg, ipr, to = gen.make_workload(args.workload)
     n_images, n_tiles = int(ipr.sum()), int(to[-1])

@@ -88,3 +88,48 @@ def test_image_instance_pipeline_matches_the_oracle_per_request():
     handoff.close()
     for e in encoders:
         e.close()
+
+
+def test_real_time_instance_encodes_every_image_once_and_as_if_alone():
+    """`ImageInstance.run_stream` on a seeded request stream that arrives faster than single launches drain it,
+    so launches of several images form: every image is encoded exactly once, a request's latency is at least
+    the duration of the launch that finished it, launches respect the maximum batch, and the tokens of an image
+    are bit for bit those of that image encoded alone (an image does not see what it is batched with)."""
+    import torch
+
+    import paper_2502_00937_amd as V
+    from paper_2502_00937_amd.image_instance import ImageInstance
+
+    cfg = gen.get_config("test_medium_bf16")
+    T = gen.tokens_per_tile(cfg)
+    enc = V.VitEncoder(cfg, gen.make_weights(cfg, seed=0), device=0)
+    pool = torch.from_numpy(gen.make_pixels(cfg, 24, seed=4)).cuda()
+    rng = np.random.default_rng(11)
+    arrivals, t = [], 0.0
+    for _ in range(40):
+        t += float(rng.exponential(0.15))            # ms: much shorter than a launch
+        arrivals.append((t, [int(x) for x in rng.integers(1, 4, size=int(rng.integers(1, 5)))]))
+    say(f"case real-time instance: {len(arrivals)} requests, {sum(len(a[1]) for a in arrivals)} images")
+    index = lambda r, k, tiles: (5 * r + 3 * k) % (24 - tiles + 1)  # noqa: E731
+    seen = {}
+
+    def on_launch(items, out, to):
+        for j, it in enumerate(items):
+            key = (it.request_id, it.image_index)
+            assert key not in seen
+            seen[key] = out[int(to[j]) * T:int(to[j + 1]) * T].clone()
+
+    inst = ImageInstance(enc, pool, max_images=6, pool_index=index)
+    latency, launches = inst.run_stream(arrivals, on_launch)
+    assert len(seen) == sum(len(a[1]) for a in arrivals)
+    assert all(1 <= n <= 6 for n, _, _ in launches) and max(n for n, _, _ in launches) > 1
+    assert sum(n for n, _, _ in launches) == len(seen)
+    assert min(latency) >= min(ms for _, _, ms in launches) > 0.0
+    say(f"    {len(launches)} launches, up to {max(n for n, _, _ in launches)} images; latency max {max(latency):.2f} ms")
+    for (r, k), got in list(seen.items())[::7]:
+        tiles = arrivals[r][1][k]
+        first = index(r, k, tiles)
+        alone, _ = enc.encode(pool[first:first + tiles], [1], np.array([0, tiles], dtype=np.int32))
+        torch.cuda.synchronize()
+        assert torch.equal(alone.view(torch.int16), got.view(torch.int16)), (r, k)
+    enc.close()

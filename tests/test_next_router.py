@@ -91,3 +91,12 @@ def test_image_level_routing_cuts_the_tail_of_a_burst():
     assert img[0] < req[0]          # the big request finishes earlier when its images run in parallel
     assert max(img) < max(req)      # and nobody waits behind it for 16 images on one instance
     assert len(img) == len(arrivals) and all(x > 0 for x in img)
+
+
+def test_percentiles_are_order_statistics():
+    from paper_2502_00937_amd.image_instance import percentiles
+
+    v = list(range(1, 101))                        # 1 ... 100: the q-th percentile is q
+    assert percentiles(v) == [50.0, 90.0, 99.0]
+    assert percentiles([7.0]) == [7.0, 7.0, 7.0]
+    assert percentiles([3.0, 1.0, 2.0], qs=(34, 100)) == [2.0, 3.0]
