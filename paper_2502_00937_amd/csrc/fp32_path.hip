@@ -57,7 +57,7 @@ __global__ __launch_bounds__(256) void gemm_f32_kernel(const GemmArgs a) {
 // One workgroup = 64 query rows x one head; 4 adjacent lanes share a query row, each owning a
 // quarter of the head dimension.  Keys/values are staged in LDS 64 at a time; softmax is the
 // running-max / running-sum form, all in fp32.
-constexpr int F32_BQ = 64, F32_BK = 64, F32_DQ_MAX = 32;
+constexpr int F32_BK = 64, F32_DQ_MAX = 32;  // (the 64 query rows are what attention_q_block reports for fp32)
 
 __global__ __launch_bounds__(256) void attention_f32_kernel(const AttnArgs a) {
   extern __shared__ float smem_f[];
