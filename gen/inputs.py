@@ -119,7 +119,7 @@ def make_workload(name: str):
 
 __all__ = [
     "CFG3_IMAGES_PER_REQUEST", "CFG4_TILES_PER_IMAGE", "round_to_bf16", "make_weights",
-    "make_pixels", "make_workload", "make_image_u8", "tokens_per_tile",
+    "make_pixels", "make_workload", "make_image_u8", "make_arrivals", "tokens_per_tile",
 ]
 
 
