@@ -5,7 +5,7 @@
 //
 // Two kernels share the fragment layout and the epilogues; both move their operands global -> LDS
 // directly (global_load_lds_dwordx4) and are described where they are defined:
-// * gemm_bf16_ring_kernel (below 384 tiles of 256 x 256): one 128 x 128 tile per workgroup, eight
+// * gemm_bf16_ring_kernel (below 384 tiles of 256 x 256): one 128 x 128 (or 64 x 128) tile per workgroup, eight
 //   waves of 64 x 32, a ring of four (or two) 64-wide k-stages;
 // * gemm_bf16_dma_kernel (everything large): persistent, 256 x 256 tiles, eight waves of 128 x 64,
 //   two 64-wide k-stages.
@@ -533,13 +533,20 @@ __global__ __launch_bounds__(512) void gemm_bf16_dma_kernel(const GemmArgs a, in
 //   grid of 1.2 or 1.7 rounds no longer costs 2.
 // (The register-staged predecessor spent 2 800 clocks per k-stage on 512 clocks of MFMA work: LDS
 // writes, their waits and un-overlapped fragment reads.)
-constexpr int R_BM = 128, R_BN = 128;
-constexpr int R_STAGE_BYTES = (R_BM + R_BN) * D_ROW;  // 32 KiB
+// * BM = 64 (a 64 x 128 tile, waves of 32 x 32, 24 KiB stages) for the very smallest products, one or two
+//   images: twice the workgroups on the idle units, and a k-stage that is a third shorter because it
+//   moves a third less through LDS (a single image's fc2 is a chain of 64 stages on 40 units otherwise).
+//   A token's k-steps are added in the same order in every variant.
+constexpr int R_BN = 128;
+constexpr int ring_stage_bytes(int bm) { return (bm + R_BN) * D_ROW; }  // 32 KiB (BM = 128) or 24 KiB
 
-template <int EPI, int R_NS>
+template <int EPI, int R_NS, int BM>
 __global__ __launch_bounds__(512) void gemm_bf16_ring_kernel(const GemmArgs a, int tiles_m, int tiles_n,
                                                              int mt_per_xcd, int n_bands) {
-  constexpr int FM = 2, FN = 1, TM = 64, TN = 32;
+  static_assert(BM == 128 || BM == 64, "tile heights: 128 or 64 rows");
+  constexpr int R_BM = BM, R_STAGE_BYTES = ring_stage_bytes(BM);
+  constexpr int FM = BM / 64, FN = 1, TM = BM / 2, TN = 32;
+  constexpr int LOADS = BM == 128 ? 4 : 3;  // direct-to-LDS instructions per wave and stage
   static_assert(8 * 32 * (TN * 4 + 16) <= R_NS * R_STAGE_BYTES, "epilogue staging must fit in the ring");
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
 
@@ -558,12 +565,15 @@ __global__ __launch_bounds__(512) void gemm_bf16_ring_kernel(const GemmArgs a, i
   const int wm = wave >> 2, wn = wave & 3;
   const int lrow = lane & 31, lk = lane >> 5;
 
-  // ---- loader: an instruction fills 8 rows of 128 bytes; wave w moves rows [16w, 16w + 16) of both
-  //      operand tiles.  The chunk that lands in LDS chunk c of row r is c ^ ((r >> 1) & 7).
+  // ---- loader: an instruction fills 8 rows of 128 bytes; wave w moves rows [16w, 16w + 16) of a 128-row
+  //      operand tile (two instructions) or rows [8w, 8w + 8) of the 64-row A tile (one).  The chunk that
+  //      lands in LDS chunk c of row r is c ^ ((r >> 1) & 7).
   const int ld_row = wave * 16 + (lane >> 3);
   const int ld_chunk = (lane & 7) ^ (lane >> 4);
-  const uint32_t offA0 = (uint32_t)(ld_row * a.lda + ld_chunk * 8) * 2u;
-  const uint32_t offA1 = (uint32_t)((ld_row + 8) * a.lda + (ld_chunk ^ 4) * 8) * 2u;
+  const int a_row = BM == 128 ? ld_row : wave * 8 + (lane >> 3);
+  const int a_chunk = BM == 128 ? ld_chunk : ld_chunk ^ (4 * (wave & 1));
+  const uint32_t offA0 = (uint32_t)(a_row * a.lda + a_chunk * 8) * 2u;
+  const uint32_t offA1 = (uint32_t)((ld_row + 8) * a.lda + (ld_chunk ^ 4) * 8) * 2u;  // BM = 128 only
   const uint32_t offW0 = (uint32_t)(ld_row * a.ldw + ld_chunk * 8) * 2u;
   const uint32_t offW1 = (uint32_t)((ld_row + 8) * a.ldw + (ld_chunk ^ 4) * 8) * 2u;
   const unsigned char* const baseA = (const unsigned char*)a.A + (size_t)m0 * a.lda * 2;
@@ -573,14 +583,18 @@ __global__ __launch_bounds__(512) void gemm_bf16_ring_kernel(const GemmArgs a, i
     asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, %2" ::"s"(lds_addr), "v"(goff), "s"(gbase)
                  : "memory", "m0");
   };
-  auto issue_stage = [&](int slot, int kt) {  // four instructions per wave
-    unsigned char* base = smem + slot * R_STAGE_BYTES + wave * 16 * D_ROW;
+  auto issue_stage = [&](int slot, int kt) {  // LOADS instructions per wave
+    unsigned char* stage = smem + slot * R_STAGE_BYTES;
     const unsigned char* ga = baseA + kt * D_ROW;
     const unsigned char* gw = baseW + kt * D_ROW;
-    dma16(ga, offA0, base);
-    dma16(ga, offA1, base + 8 * D_ROW);
-    dma16(gw, offW0, base + R_BM * D_ROW);
-    dma16(gw, offW1, base + R_BM * D_ROW + 8 * D_ROW);
+    if constexpr (BM == 128) {
+      dma16(ga, offA0, stage + wave * 16 * D_ROW);
+      dma16(ga, offA1, stage + wave * 16 * D_ROW + 8 * D_ROW);
+    } else {
+      dma16(ga, offA0, stage + wave * 8 * D_ROW);
+    }
+    dma16(gw, offW0, stage + R_BM * D_ROW + wave * 16 * D_ROW);
+    dma16(gw, offW1, stage + R_BM * D_ROW + wave * 16 * D_ROW + 8 * D_ROW);
   };
 
   const int sw = (lrow >> 1) & 7;
@@ -604,7 +618,7 @@ __global__ __launch_bounds__(512) void gemm_bf16_ring_kernel(const GemmArgs a, i
     const int slot = kt & (R_NS - 1);
     // this wave's loads of stage kt have landed (those of the two later stages may be in flight) and
     // its LDS reads of stage kt - 1 are complete; then meet the other waves
-    __builtin_amdgcn_s_waitcnt(0x0070 | (4 * (R_NS - 2)));
+    __builtin_amdgcn_s_waitcnt(0x0070 | (LOADS * (R_NS - 2)));
     __builtin_amdgcn_s_barrier();
     issue_stage((kt + R_NS - 1) & (R_NS - 1), min(kt + R_NS - 1, KT - 1));
     const unsigned char* st = smem + slot * R_STAGE_BYTES;
@@ -629,7 +643,13 @@ __global__ __launch_bounds__(512) void gemm_bf16_ring_kernel(const GemmArgs a, i
 }
 
 hipError_t launch_ring(const GemmArgs& a, hipStream_t s) {
-  const int tiles_m = (a.M + R_BM - 1) / R_BM, tiles_n = (a.N + R_BN - 1) / R_BN;
+  const int tiles_n = (a.N + R_BN - 1) / R_BN;
+  // At most 96 tiles of 128 x 128 (the N = 1024 products of one or two images): 64-row tiles, still fewer
+  // workgroups than units.  Measured at 577 and 1154 rows: 40 and 80 tiles gain 30-45 %, 120 tiles (QKV of
+  // one image) lose 15 %.
+  const bool half = (long)((a.M + 127) / 128) * tiles_n <= 96;
+  const int bm = half ? 64 : 128;
+  const int tiles_m = (a.M + bm - 1) / bm;
   const int mt_per_xcd = (tiles_m + 7) / 8;
   const int n_bands = (tiles_n + GROUP_N - 1) / GROUP_N;
   const int m_blocks = (mt_per_xcd + GROUP_M - 1) / GROUP_M;
@@ -638,20 +658,22 @@ hipError_t launch_ring(const GemmArgs& a, hipStream_t s) {
   // More tiles than compute units: two-stage rings (64 KiB) so that two workgroups share a unit and
   // the rounds overlap; otherwise the four-stage ring, whose loads run three stages ahead.
   const bool two = (long)tiles_m * tiles_n > 256;
-#define VIT_LAUNCH_NS(EPI, NS)                                                                                       \
+#define VIT_LAUNCH_NS(EPI, NS, BM)                                                                                   \
   do {                                                                                                               \
-    auto kfn = gemm_bf16_ring_kernel<EPI, NS>;                                                                       \
-    constexpr int lds = NS * R_STAGE_BYTES;                                                                          \
+    auto kfn = gemm_bf16_ring_kernel<EPI, NS, BM>;                                                                   \
+    constexpr int lds = NS * ring_stage_bytes(BM);                                                                   \
     static LdsLimitOnce lds_limit;                                                                                   \
     if (hipError_t e = lds_limit.ensure((const void*)kfn, lds); e != hipSuccess) return e;                           \
     hipLaunchKernelGGL(kfn, dim3((unsigned)grid), dim3(512), lds, s, a, tiles_m, tiles_n, mt_per_xcd, n_bands);      \
   } while (0)
-#define VIT_LAUNCH(EPI)           \
-  do {                            \
-    if (two)                      \
-      VIT_LAUNCH_NS(EPI, 2);      \
-    else                          \
-      VIT_LAUNCH_NS(EPI, 4);      \
+#define VIT_LAUNCH(EPI)            \
+  do {                             \
+    if (half)                      \
+      VIT_LAUNCH_NS(EPI, 4, 64);   \
+    else if (two)                  \
+      VIT_LAUNCH_NS(EPI, 2, 128);  \
+    else                           \
+      VIT_LAUNCH_NS(EPI, 4, 128);  \
   } while (0)
   switch (a.epilogue) {
     case EPI_BIAS: VIT_LAUNCH(EPI_BIAS); break;

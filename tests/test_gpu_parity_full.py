@@ -77,9 +77,10 @@ def test_cfg6_6b_downsampled_sampled():
 
 def test_tokens_are_bit_identical_at_every_batch_size():
     """An image's tokens do not depend on how many images share its launch: 1, 2 and 8 images run every
-    product on the 128 x 128 ring kernel (four- and two-stage rings), 64 images mix both matrix-product
-    kernels, 260 images run the persistent 256 x 256 kernel, and all of them add a token's k-steps in the
-    same order.  Compared bit for bit against the full config-3 batch."""
+    product on the ring kernel (four- and two-stage rings; 1 and 2 images with its 64-row tiles for the
+    narrow products), 64 images mix both matrix-product kernels, 260 images run the persistent 256 x 256
+    kernel, and all of them add a token's k-steps in the same order.  Compared bit for bit against the
+    full config-3 batch."""
     import torch
 
     import paper_2502_00937_amd as V
