@@ -183,6 +183,17 @@ def test_error_paths_launch_nothing():
     with pytest.raises(V.VitError) as ei:      # negative image count
         V.vit_encode_packed(enc.handle, px.data_ptr(), [-1], [0], out.data_ptr(), out_bytes, ws.data_ptr(), ws_bytes)
     assert ei.value.status == B.VIT_EINVAL
+    # more token rows than the 32-bit row indices of the kernels hold: refused before anything is sized or touched
+    T = gen.tokens_per_tile(cfg)
+    too_many = (2 ** 31) // T + 1
+    with pytest.raises(V.VitError) as ei:
+        V.vit_encode_packed(enc.handle, px.data_ptr(), [1], [0, too_many], out.data_ptr(), out_bytes, ws.data_ptr(),
+                            ws_bytes)
+    assert ei.value.status == B.VIT_EINVAL
+    with pytest.raises(V.VitError) as ei:
+        enc.query(too_many, 1)
+    assert ei.value.status == B.VIT_EINVAL
+    assert enc.query((2 ** 31 - 2048) // T, 1)[0] == ((2 ** 31 - 2048) // T) * T   # just below the limit: sized, not run
     torch.cuda.synchronize()
     assert bool((out == 7.0).all())
     enc.close()
