@@ -103,3 +103,16 @@ def test_tokens_are_bit_identical_at_every_batch_size():
     torch.cuda.synchronize()
     assert torch.equal(tail.view(torch.int16), full[257 * T:].view(torch.int16))
     enc.close()
+
+
+def test_buffers_of_more_than_2_31_elements():
+    """The config-4 encoder over 700 tiles (510 300 tokens): the fc1 output holds 2.22e9 elements and the QKV
+    buffer 1.96e9, so element indices pass 2^31 and byte offsets 2^32 in every large buffer.  The first image and
+    the last one (the highest rows of every buffer) are compared with the oracle."""
+    cfg = gen.get_config("cfg4_siglip_384")
+    tpi = [5] * 140
+    T = gen.tokens_per_tile(cfg)
+    assert sum(tpi) * T * 4352 > 2 ** 31 and sum(tpi) * T < 2 ** 31 - 1024
+    say(f"case 2^31 elements: {sum(tpi)} tiles, {sum(tpi) * T} tokens")
+    got, _ = check_case(cfg, tpi, [1] * len(tpi), images=[0, 139], oracle_dtype=np.float32, label="2^31")
+    assert got.shape == (sum(tpi) * T, 4096)
