@@ -162,7 +162,7 @@ vit_status_t vit_profile_read(vit_encoder_t* enc, double* ms, int64_t* launches)
  * them from the producers' addresses).  Host-side table of device pointers and events; the
  * only device work is the copy queued by vit_handoff_pull.  All functions are thread-safe.
  *
- *   vit_handoff_expect   announces request `request_id` with n_images (> 0) images.
+ *   vit_handoff_expect   announces request `request_id` with n_images (1 ... 65536) images.
  *   vit_handoff_publish  image `image_index` of the request lies at `tokens` (device memory,
  *                        `bytes` > 0 long) once the work queued so far on `stream` (hipStream_t;
  *                        NULL = null stream) has finished: an event is recorded there.  The

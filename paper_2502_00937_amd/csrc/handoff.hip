@@ -66,10 +66,16 @@ void vit_handoff_destroy(vit_handoff_t* h) {
 }
 
 vit_status_t vit_handoff_expect(vit_handoff_t* h, int64_t request_id, int32_t n_images) {
-  if (!h || n_images <= 0) return set_error(VIT_EINVAL, "vit_handoff_expect: bad argument");
+  if (!h || n_images <= 0 || n_images > 65536)
+    return set_error(VIT_EINVAL, "vit_handoff_expect: need a handle and 1 <= n_images <= 65536");
   std::lock_guard<std::mutex> lock(h->mu);
   if (h->requests.count(request_id)) return set_error(VIT_EINVAL, "vit_handoff_expect: request %lld is already known", (long long)request_id);
-  h->requests[request_id].pieces.resize((size_t)n_images);
+  try {
+    h->requests[request_id].pieces.resize((size_t)n_images);
+  } catch (...) {  // out of host memory: nothing of the request stays behind
+    h->requests.erase(request_id);
+    return set_error(VIT_ENOMEM, "vit_handoff_expect: out of host memory for %d images", n_images);
+  }
   return VIT_OK;
 }
 

@@ -235,9 +235,19 @@ struct ProfScope {
     if (start && stop) (void)hipEventRecord(start, s);
   }
   ~ProfScope() {
-    if (!e->profiling || !start || !stop) return;
+    if (!start || !stop) {  // an event could not be created: the launch goes untimed, nothing is kept
+      if (start) (void)hipEventDestroy(start);
+      if (stop) (void)hipEventDestroy(stop);
+      return;
+    }
+    if (!e->profiling) return;
     (void)hipEventRecord(stop, s);
-    e->prof.push_back({family, start, stop});
+    try {
+      e->prof.push_back({family, start, stop});
+    } catch (...) {  // out of host memory: this one launch goes untimed
+      (void)hipEventDestroy(start);
+      (void)hipEventDestroy(stop);
+    }
   }
 };
 
@@ -367,7 +377,7 @@ vit_status_t vit_encoder_create(const vit_config_t* cfg, const float* weights, s
       in = dout;
       in_ld = d.proj0_ld;
     }
-  } catch (const std::bad_alloc&) {
+  } catch (...) {  // bad_alloc, or length_error from a size no vector can hold
     delete e;
     return fail(VIT_ENOMEM, "vit_encoder_create: out of host memory while laying out weights");
   }
@@ -636,6 +646,11 @@ vit_status_t vit_encode_packed(vit_encoder_t* e, const float* pixels, const int3
 vit_status_t vit_profile_enable(vit_encoder_t* e, int enable) {
   if (!e) return fail(VIT_EINVAL, "vit_profile_enable: NULL encoder");
   HIP_TRY(hipSetDevice(e->device));
+  try {
+    e->free_events.reserve(e->free_events.size() + 2 * e->prof.size());
+  } catch (...) {
+    return fail(VIT_ENOMEM, "vit_profile_enable: out of host memory");
+  }
   for (auto& r : e->prof) {
     HIP_TRY(hipEventSynchronize(r.stop));
     e->free_events.push_back(r.start);
@@ -650,6 +665,11 @@ vit_status_t vit_profile_enable(vit_encoder_t* e, int enable) {
 vit_status_t vit_profile_read(vit_encoder_t* e, double* ms, int64_t* launches) {
   if (!e || !ms || !launches) return fail(VIT_EINVAL, "vit_profile_read: NULL argument");
   HIP_TRY(hipSetDevice(e->device));
+  try {
+    e->free_events.reserve(e->free_events.size() + 2 * e->prof.size());
+  } catch (...) {
+    return fail(VIT_ENOMEM, "vit_profile_read: out of host memory");
+  }
   for (auto& r : e->prof) {
     HIP_TRY(hipEventSynchronize(r.stop));
     float t = 0.f;

@@ -171,6 +171,11 @@ def test_handoff_table_logic_without_a_device():
     assert e.value.status == -1 and "already known" in str(e.value)
     with pytest.raises(V.VitError):
         h.expect(8, 0)
+    with pytest.raises(V.VitError) as e:
+        h.expect(8, 65537)                  # more images than a request may announce
+    assert e.value.status == -1
+    h.expect(8, 65536)
+    h.release(8)
     assert h.complete(7) == (False, 0)
     assert h.complete(99) == (False, 0)
     with pytest.raises(V.VitError) as e:
