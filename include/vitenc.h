@@ -42,19 +42,19 @@ enum { VIT_DTYPE_FP32 = 0, VIT_DTYPE_BF16 = 1 };
  * (Table 1: 448/14 = 32, merged 2 x 2 -> 256).
  */
 typedef struct {
-  int32_t image_size;    /* S: tiles are S x S pixels                                           */
-  int32_t patch_size;    /* p                                                                   */
-  int32_t channels;      /* C (3)                                                               */
+  int32_t image_size;    /* S: tiles are S x S pixels; floor(S / p) <= 512                      */
+  int32_t patch_size;    /* p <= 256                                                            */
+  int32_t channels;      /* C (3); <= 16                                                        */
   int32_t hidden;        /* D, divisible by heads                                               */
   int32_t heads;         /* H; head dim D/H must be <= 128 and a multiple of 8                  */
-  int32_t mlp;           /* M: width of the block MLP                                           */
-  int32_t layers_local;  /* blocks whose attention segment is one tile                          */
+  int32_t mlp;           /* M: width of the block MLP, a multiple of 8, <= 65536                */
+  int32_t layers_local;  /* blocks whose attention segment is one tile (each count <= 1024)     */
   int32_t layers_global; /* following blocks whose attention segment is all tiles of one image  */
   int32_t has_cls;       /* 1: a learned CLS row precedes the patches of every tile             */
   int32_t final_ln;      /* 1: LayerNorm after the last block                                   */
   float ln_eps;          /* added to the biased variance                                        */
   int32_t proj_layers;   /* 0, 1 or 2 linear layers after the encoder, GELU between them        */
-  int32_t proj_dims[2];  /* output width of each projector layer                                */
+  int32_t proj_dims[2];  /* output width of each projector layer, multiples of 8, <= 65536      */
   int32_t dtype;         /* VIT_DTYPE_FP32: fp32 arithmetic and output;                         */
                          /* VIT_DTYPE_BF16: bf16 matrix operands, fp32 accumulation and         */
                          /* residual stream, bf16 output                                        */

@@ -74,17 +74,28 @@ bool derive(const vit_config_t* c, Dims* d, const char** why) {
     *why = "image_size, patch_size, channels must be positive and patch_size <= image_size";
     return false;
   }
+  // bounds that keep every derived count (tokens per tile, patch vector length, T * D) inside 32 bits
+  if (c->channels > 16 || c->patch_size > 256 || c->image_size / c->patch_size > 512) {
+    *why = "channels <= 16, patch_size <= 256 and floor(image_size / patch_size) <= 512";
+    return false;
+  }
   if (c->hidden <= 0 || c->heads <= 0 || c->hidden % c->heads != 0) { *why = "hidden must be a positive multiple of heads"; return false; }
   const int dh = c->hidden / c->heads;
   if (dh % 8 != 0 || dh > 128) { *why = "head dim must be a multiple of 8 and <= 128"; return false; }
-  if (c->mlp <= 0 || c->mlp % 8 != 0) { *why = "mlp must be a positive multiple of 8"; return false; }
-  if (c->layers_local < 0 || c->layers_global < 0) { *why = "layer counts must be >= 0"; return false; }
+  if (c->mlp <= 0 || c->mlp % 8 != 0 || c->mlp > 65536) { *why = "mlp must be a positive multiple of 8, at most 65536"; return false; }
+  if (c->layers_local < 0 || c->layers_global < 0 || c->layers_local > 1024 || c->layers_global > 1024) {
+    *why = "layer counts must be in [0, 1024]";
+    return false;
+  }
   if (c->has_cls != 0 && c->has_cls != 1) { *why = "has_cls must be 0 or 1"; return false; }
   if (c->final_ln != 0 && c->final_ln != 1) { *why = "final_ln must be 0 or 1"; return false; }
   if (!(c->ln_eps >= 0.f) || !std::isfinite(c->ln_eps)) { *why = "ln_eps must be finite and >= 0"; return false; }
   if (c->proj_layers < 0 || c->proj_layers > 2) { *why = "proj_layers must be 0, 1 or 2"; return false; }
   for (int i = 0; i < c->proj_layers; ++i)
-    if (c->proj_dims[i] <= 0 || c->proj_dims[i] % 8 != 0) { *why = "proj_dims must be positive multiples of 8"; return false; }
+    if (c->proj_dims[i] <= 0 || c->proj_dims[i] % 8 != 0 || c->proj_dims[i] > 65536) {
+      *why = "proj_dims must be positive multiples of 8, at most 65536";
+      return false;
+    }
   if (c->dtype != VIT_DTYPE_FP32 && c->dtype != VIT_DTYPE_BF16) { *why = "dtype must be VIT_DTYPE_FP32 or VIT_DTYPE_BF16"; return false; }
   if (c->hidden > 4096) { *why = "hidden must be <= 4096"; return false; }
   if (c->token_merge < 0 || c->token_merge > 8) { *why = "token_merge must be in [0, 8]"; return false; }

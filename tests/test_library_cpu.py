@@ -110,7 +110,10 @@ def test_weight_count_rejects_bad_configs():
     base = gen.get_config("test_small_bf16")
     for key, val in [("heads", 3), ("hidden", 0), ("patch_size", 0), ("proj_layers", 3), ("mlp", 7),
                      ("hidden", 20), ("has_cls", 2), ("layers_local", -1), ("ln_eps", float("nan")),
-                     ("token_merge", 3), ("token_merge", -1), ("token_merge", 9)]:  # 56/14 = 4 is no multiple of 3
+                     ("token_merge", 3), ("token_merge", -1), ("token_merge", 9),  # 56/14 = 4 is no multiple of 3
+                     # sizes whose derived counts would leave 32 bits
+                     ("channels", 17), ("mlp", 65544), ("layers_local", 1025), ("layers_global", 1025),
+                     ("image_size", 56 * 1000), ("patch_size", 257)]:
         cfg = dict(base)
         cfg[key] = val
         if key == "proj_layers":
