@@ -72,8 +72,8 @@ extern "C" vit_status_t vit_preprocess_tiles(const uint8_t* image, int32_t heigh
   if (height <= 0 || width <= 0 || channels <= 0 || channels > 4 || tile_size <= 0 || grid_rows <= 0 || grid_cols <= 0)
     return set_error(VIT_EINVAL, "vit_preprocess_tiles: sizes must be positive and channels <= 4");
   if ((int64_t)grid_rows * grid_cols + 1 > 65535 || (int64_t)tile_size * tile_size > (int64_t)1 << 30 ||
-      (int64_t)height * width * channels > (int64_t)1 << 40)
-    return set_error(VIT_EINVAL, "vit_preprocess_tiles: at most 65534 tiles of at most 2^30 pixels");
+      (int64_t)height * width * channels > (int64_t)1 << 40 || (int64_t)width * channels > INT32_MAX)
+    return set_error(VIT_EINVAL, "vit_preprocess_tiles: at most 65534 tiles of at most 2^30 pixels, image rows below 2^31 bytes");
   PrepArgs a;
   for (int c = 0; c < channels; ++c) {
     if (!(std_[c] > 0.f) || !std::isfinite(std_[c]) || !std::isfinite(mean[c]))
