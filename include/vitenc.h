@@ -131,6 +131,29 @@ vit_status_t vit_encode_packed(vit_encoder_t* enc, const float* pixels,
                                size_t out_capacity_bytes, int64_t* request_token_offsets,
                                void* workspace, size_t workspace_bytes, void* stream);
 
+/*
+ * vit_encode_packed for callers that cannot allocate: code under HIP graph capture, tight serving
+ * loops, harnesses that forbid hipMalloc.  Same arguments, results and errors as vit_encode_packed
+ * minus the workspace: the call carves its workspace out of a static device array of
+ * VIT_STATIC_SCRATCH_BYTES that each GPU the library runs on holds until the process ends, writes
+ * its attention work lists with a small kernel (no pinned staging buffer, no host-to-device copy),
+ * and calls no hipMalloc / hipHostMalloc / hipFree / hipEventCreate or other allocating routine;
+ * per-kernel timing (vit_profile_enable) does not cover it.
+ * Limits: the batch's vit_encoder_query workspace_bytes must not exceed VIT_STATIC_SCRATCH_BYTES
+ * (128 MiB: eight 336-px images of a ViT-L/14 encoder) and it may hold at most
+ * VIT_STATIC_MAX_IMAGES images; beyond either the call returns VIT_ECAPACITY and launches nothing.
+ * All calls on one GPU, from any handle, share that GPU's array: calls whose device work overlaps
+ * (different streams or threads) race; calls queued on one stream do not.  The array keeps the
+ * previous call's contents; every call rewrites all it reads.
+ */
+#define VIT_STATIC_SCRATCH_BYTES ((size_t)128 << 20)
+#define VIT_STATIC_MAX_IMAGES 256
+vit_status_t vit_encode_packed_static(vit_encoder_t* enc, const float* pixels,
+                                      const int32_t* images_per_request, int32_t n_requests,
+                                      const int32_t* tile_offsets, void* out_tokens,
+                                      size_t out_capacity_bytes, int64_t* request_token_offsets,
+                                      void* stream);
+
 /* Free device weights and the handle.  NULL is allowed.  The caller must have drained
  * every stream the handle was used on. */
 void vit_encoder_destroy(vit_encoder_t* enc);

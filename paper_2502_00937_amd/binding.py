@@ -11,6 +11,7 @@ _LIB = None
 
 VIT_OK, VIT_EINVAL, VIT_ENOMEM, VIT_ECAPACITY, VIT_EDEVICE = 0, -1, -2, -3, -4
 VIT_DTYPE_FP32, VIT_DTYPE_BF16 = 0, 1
+VIT_STATIC_SCRATCH_BYTES, VIT_STATIC_MAX_IMAGES = 128 << 20, 256
 PROF_FAMILIES = ("patchify", "gemm", "layernorm", "attention")
 
 
@@ -55,6 +56,9 @@ def load_library():
     lib.vit_encode_packed.restype = C.c_int
     lib.vit_encode_packed.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32, C.c_void_p, C.c_void_p, C.c_size_t,
                                       C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]
+    lib.vit_encode_packed_static.restype = C.c_int
+    lib.vit_encode_packed_static.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32, C.c_void_p, C.c_void_p,
+                                             C.c_size_t, C.c_void_p, C.c_void_p]
     lib.vit_encoder_destroy.restype = None
     lib.vit_encoder_destroy.argtypes = [C.c_void_p]
     lib.vit_profile_enable.restype = C.c_int
@@ -135,6 +139,20 @@ def vit_encode_packed(handle: int, pixels_ptr: int, images_per_request, tile_off
     _check(load_library().vit_encode_packed(handle, pixels_ptr, ipr.ctypes.data if ipr.size else None, ipr.size,
                                             to.ctypes.data, out_ptr, out_capacity_bytes, rto.ctypes.data,
                                             workspace_ptr, workspace_bytes, stream))
+    return rto
+
+
+def vit_encode_packed_static(handle: int, pixels_ptr: int, images_per_request, tile_offsets, out_ptr: int,
+                             out_capacity_bytes: int, stream: int = 0):
+    """Raw call of the allocation-free variant (workspace = the library's static device array)."""
+    ipr = np.ascontiguousarray(images_per_request, dtype=np.int32)
+    to = np.ascontiguousarray(tile_offsets, dtype=np.int32)
+    if (ipr >= 0).all() and to.size != int(ipr.sum()) + 1:
+        raise VitError(VIT_EINVAL, "tile_offsets must have sum(images_per_request) + 1 entries")
+    rto = np.zeros(ipr.size + 1, dtype=np.int64)
+    _check(load_library().vit_encode_packed_static(handle, pixels_ptr, ipr.ctypes.data if ipr.size else None, ipr.size,
+                                                   to.ctypes.data, out_ptr, out_capacity_bytes, rto.ctypes.data,
+                                                   stream))
     return rto
 
 

@@ -177,6 +177,8 @@ struct vit_encoder {
   int device = 0;
   unsigned char* dev_weights = nullptr;
   size_t dev_weight_bytes = 0;
+  unsigned char* scratch = nullptr;  // this device's copy of the static scratch array (vit_encode_packed_static)
+  hipError_t scratch_error = hipSuccess;
   Linear patch, proj[2];
   const float *cls = nullptr, *pos = nullptr, *lnf_g = nullptr, *lnf_b = nullptr;
   std::vector<Layer> layers;
@@ -239,8 +241,8 @@ struct ProfScope {
   hipStream_t s;
   int family;
   hipEvent_t start = nullptr, stop = nullptr;
-  ProfScope(vit_encoder* e_, hipStream_t s_, int family_) : e(e_), s(s_), family(family_) {
-    if (!e->profiling) return;
+  ProfScope(vit_encoder* e_, hipStream_t s_, int family_, bool on = true) : e(e_), s(s_), family(family_) {
+    if (!on || !e->profiling) return;
     start = get_event(e);
     stop = get_event(e);
     if (start && stop) (void)hipEventRecord(start, s);
@@ -261,6 +263,54 @@ struct ProfScope {
     }
   }
 };
+
+// ---- the allocation-free entry point's device memory -------------------------------------------
+// One array per GPU the library runs on, held until the process ends.  Every vit_encode_packed_static
+// call on a GPU carves its workspace out of that GPU's copy.
+constexpr size_t kStaticScratchBytes = VIT_STATIC_SCRATCH_BYTES;
+constexpr int kStaticMaxImages = VIT_STATIC_MAX_IMAGES;
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+
+// In host code `scratch` is only a handle for the symbol; the array's address on a device comes from
+// hipGetSymbolAddress with that device current, looked up once per device and kept here.
+std::atomic<unsigned char*> g_scratch_ptr[64];
+
+hipError_t scratch_of_current_device(int device, unsigned char** out) {
+  *out = nullptr;
+  if (device < 0 || device >= 64) return hipErrorInvalidDevice;
+  unsigned char* p = g_scratch_ptr[device].load(std::memory_order_acquire);
+  if (!p) {
+    void* sym = nullptr;
+    if (hipError_t e = hipGetSymbolAddress(&sym, HIP_SYMBOL(scratch)); e != hipSuccess) return e;
+    if (!sym) return hipErrorInvalidSymbol;
+    p = (unsigned char*)sym;
+    g_scratch_ptr[device].store(p, std::memory_order_release);
+  }
+  *out = p;
+  return hipSuccess;
+}
+
+// Attention work lists written on the device from tile offsets that travel as a kernel argument (no
+// staging buffer, no copy).  Same order as the host-built lists: query blocks of tile 0, tile 1, ...;
+// then, for global layers, query blocks of image 0, image 1, ...
+struct TileOffsetsArg { int32_t v[kStaticMaxImages + 1]; };
+
+__global__ __launch_bounds__(256) void attn_work_kernel(const TileOffsetsArg to, int n_images, int T, int bq,
+                                                        AttnWork* __restrict__ loc, AttnWork* __restrict__ glob) {
+  const int n_tiles = to.v[n_images];
+  const int nb = (T + bq - 1) / bq;
+  for (int idx = threadIdx.x; idx < n_tiles * nb; idx += 256) {
+    const int t = idx / nb, j = idx - t * nb;
+    loc[idx] = AttnWork{t * T + j * bq, t * T, T};
+  }
+  if (!glob) return;
+  for (int i = threadIdx.x; i < n_images; i += 256) {
+    int first = 0;
+    for (int k = 0; k < i; ++k) first += ((to.v[k + 1] - to.v[k]) * T + bq - 1) / bq;
+    const int start = to.v[i] * T, len = (to.v[i + 1] - to.v[i]) * T;
+    for (int q = 0, n = 0; q < len; q += bq, ++n) glob[first + n] = AttnWork{start + q, start, len};
+  }
+}
 
 // Register-only MFMA loop: eight independent 32x32 accumulators per wave, no memory traffic inside the
 // loop.  What it sustains is the matrix cores' practical ceiling on this device: the clock the chip
@@ -411,6 +461,9 @@ vit_status_t vit_encoder_create(const vit_config_t* cfg, const float* weights, s
     p.dst->bias = (const float*)(e->dev_weights + p.b_off);
   }
   for (auto& p : pptr) *p.dst = (const float*)(e->dev_weights + p.off);
+  // the static scratch array's address on this device (which is current here); a failure only disables
+  // vit_encode_packed_static, which then reports it
+  e->scratch_error = scratch_of_current_device(device, &e->scratch);
   *out = e;
   return VIT_OK;
 }
@@ -484,27 +537,30 @@ vit_status_t vit_encoder_query(const vit_encoder_t* e, int32_t n_tiles, int32_t 
   return VIT_OK;
 }
 
-vit_status_t vit_encode_packed(vit_encoder_t* e, const float* pixels, const int32_t* images_per_request,
-                               int32_t n_requests, const int32_t* tile_offsets, void* out_tokens,
-                               size_t out_capacity_bytes, int64_t* request_token_offsets, void* workspace,
-                               size_t workspace_bytes, void* stream) {
-  if (!e) return fail(VIT_EINVAL, "vit_encode_packed: NULL encoder");
-  if (n_requests < 0) return fail(VIT_EINVAL, "vit_encode_packed: n_requests < 0");
-  if (n_requests > 0 && !images_per_request) return fail(VIT_EINVAL, "vit_encode_packed: images_per_request is NULL");
-  if (!tile_offsets) return fail(VIT_EINVAL, "vit_encode_packed: tile_offsets is NULL");
+// The encode path behind both entry points.  `static_scratch`: the workspace is the calling device's
+// static array, the attention work lists are written by a kernel, and nothing is allocated: no pinned
+// staging, no events (per-kernel timing is off for such a call).
+static vit_status_t encode_impl(const char* fn, vit_encoder_t* e, const float* pixels, const int32_t* images_per_request,
+                                int32_t n_requests, const int32_t* tile_offsets, void* out_tokens,
+                                size_t out_capacity_bytes, int64_t* request_token_offsets, void* workspace,
+                                size_t workspace_bytes, void* stream, bool static_scratch) {
+  if (!e) return fail(VIT_EINVAL, "%s: NULL encoder", fn);
+  if (n_requests < 0) return fail(VIT_EINVAL, "%s: n_requests < 0", fn);
+  if (n_requests > 0 && !images_per_request) return fail(VIT_EINVAL, "%s: images_per_request is NULL", fn);
+  if (!tile_offsets) return fail(VIT_EINVAL, "%s: tile_offsets is NULL", fn);
   const Dims& d = e->d;
   int64_t n_images = 0;
   for (int r = 0; r < n_requests; ++r) {
-    if (images_per_request[r] < 0) return fail(VIT_EINVAL, "vit_encode_packed: images_per_request[%d] < 0", r);
+    if (images_per_request[r] < 0) return fail(VIT_EINVAL, "%s: images_per_request[%d] < 0", fn, r);
     n_images += images_per_request[r];
   }
-  if (n_images > INT32_MAX) return fail(VIT_EINVAL, "vit_encode_packed: too many images");
-  if (tile_offsets[0] != 0) return fail(VIT_EINVAL, "vit_encode_packed: tile_offsets[0] must be 0");
+  if (n_images > INT32_MAX) return fail(VIT_EINVAL, "%s: too many images", fn);
+  if (tile_offsets[0] != 0) return fail(VIT_EINVAL, "%s: tile_offsets[0] must be 0", fn);
   for (int64_t i = 0; i < n_images; ++i)
     if (tile_offsets[i + 1] <= tile_offsets[i])
-      return fail(VIT_EINVAL, "vit_encode_packed: image %lld has no tiles (tile_offsets must increase)", (long long)i);
+      return fail(VIT_EINVAL, "%s: image %lld has no tiles (tile_offsets must increase)", fn, (long long)i);
   const int64_t n_tiles = tile_offsets[n_images];
-  if (n_tiles * d.T > (int64_t)INT32_MAX - 1024) return fail(VIT_EINVAL, "vit_encode_packed: more than 2^31 token rows");
+  if (n_tiles * d.T > (int64_t)INT32_MAX - 1024) return fail(VIT_EINVAL, "%s: more than 2^31 token rows", fn);
   if (request_token_offsets) {
     int64_t img = 0;
     request_token_offsets[0] = 0;
@@ -514,17 +570,21 @@ vit_status_t vit_encode_packed(vit_encoder_t* e, const float* pixels, const int3
     }
   }
   if (n_tiles == 0) return VIT_OK;
-  if (!pixels || !out_tokens || !workspace) return fail(VIT_EINVAL, "vit_encode_packed: NULL device buffer");
+  if (!pixels || !out_tokens || !workspace) return fail(VIT_EINVAL, "%s: NULL device buffer", fn);
   if (((uintptr_t)workspace & 255) || ((uintptr_t)out_tokens & 15) || ((uintptr_t)pixels & 15))
-    return fail(VIT_EINVAL, "vit_encode_packed: workspace must be 256-byte aligned, pixels and out_tokens 16-byte aligned");
+    return fail(VIT_EINVAL, "%s: workspace must be 256-byte aligned, pixels and out_tokens 16-byte aligned", fn);
 
   Workspace w;
   plan_workspace(d, n_tiles, &w);
   const size_t out_need = (size_t)w.n_out * d.out_dim * d.es;
   if (out_capacity_bytes < out_need)
-    return fail(VIT_ECAPACITY, "vit_encode_packed: out_tokens holds %zu bytes, %zu needed", out_capacity_bytes, out_need);
+    return fail(VIT_ECAPACITY, "%s: out_tokens holds %zu bytes, %zu needed", fn, out_capacity_bytes, out_need);
   if (workspace_bytes < w.total)
-    return fail(VIT_ECAPACITY, "vit_encode_packed: workspace holds %zu bytes, %zu needed", workspace_bytes, w.total);
+    return fail(VIT_ECAPACITY, static_scratch ? "%s: the static scratch array holds %zu bytes, this batch needs %zu"
+                                              : "%s: workspace holds %zu bytes, %zu needed",
+                fn, workspace_bytes, w.total);
+  if (static_scratch && n_images > kStaticMaxImages)
+    return fail(VIT_ECAPACITY, "%s: %lld images, at most %d per call", fn, (long long)n_images, kStaticMaxImages);
 
   HIP_TRY(hipSetDevice(e->device));
   hipStream_t s = (hipStream_t)stream;
@@ -540,8 +600,20 @@ vit_status_t vit_encode_packed(vit_encoder_t* e, const float* pixels, const int3
   // ---- segment planning: blocks of query rows per tile (local layers) and per image (global layers)
   const int bq = attention_q_block(d.bf16, d.dhp);
   const bool has_global = d.L > d.L_loc;
+  const bool timing = !static_scratch;  // events are created on demand: not in a call that may not allocate
   int n_local = 0, n_global = 0;
-  {
+  if (static_scratch) {
+    // the lists' lengths on the host (launch sizes), their contents by a kernel from the offsets themselves
+    n_local = (int)(n_tiles * ((d.T + bq - 1) / bq));
+    TileOffsetsArg to;
+    memset(&to, 0, sizeof(to));
+    for (int64_t i = 0; i <= n_images; ++i) to.v[i] = tile_offsets[i];
+    if (has_global)
+      for (int64_t i = 0; i < n_images; ++i) n_global += ((tile_offsets[i + 1] - tile_offsets[i]) * d.T + bq - 1) / bq;
+    hipLaunchKernelGGL(attn_work_kernel, dim3(1), dim3(256), 0, s, to, (int)n_images, d.T, bq, tables,
+                       has_global ? tables + w.max_work : (AttnWork*)nullptr);
+    HIP_TRY(hipGetLastError());
+  } else {
     StageSlot& slot = e->stage[e->next_stage];
     e->next_stage = (e->next_stage + 1) % 4;
     if (slot.used) HIP_TRY(hipEventSynchronize(slot.done));
@@ -582,11 +654,11 @@ vit_status_t vit_encode_packed(vit_encoder_t* e, const float* pixels, const int3
     a.reverse = reverse;
     reverse ^= 1;
     a.stream_out = (size_t)M * lin.N * d.es > kCacheBytes;
-    ProfScope ps(e, s, VIT_PROF_GEMM);
+    ProfScope ps(e, s, VIT_PROF_GEMM, timing);
     return d.bf16 ? launch_gemm_bf16(a, s) : launch_gemm_f32(a, s);
   };
   auto layernorm = [&](const float* g_, const float* b_, int normalize, void* out, int ldo, int out_cols) -> hipError_t {
-    ProfScope ps(e, s, VIT_PROF_LAYERNORM);
+    ProfScope ps(e, s, VIT_PROF_LAYERNORM, timing);
     const int rev = reverse;
     reverse ^= 1;
     return launch_layernorm(x, d.D, out, ldo, out_cols, g_, b_, d.eps, n_tok, d.D, normalize, d.bf16, rev,
@@ -595,7 +667,7 @@ vit_status_t vit_encode_packed(vit_encoder_t* e, const float* pixels, const int3
 
   // ---- patch embedding: gather -> matrix product with (+bias, +pos, row remap) epilogue; CLS rows
   {
-    ProfScope ps(e, s, VIT_PROF_PATCHIFY);
+    ProfScope ps(e, s, VIT_PROF_PATCHIFY, timing);
     HIP_TRY(launch_patch_gather(pixels, u, d.Kp_pad, (int)n_tiles, d.C, d.S, d.p, d.g, d.Kp_pad, d.bf16, s));
     if (d.has_cls) HIP_TRY(launch_cls_rows(x, d.D, e->cls, e->pos, (int)n_tiles, d.T, d.D, s));
   }
@@ -616,7 +688,7 @@ vit_status_t vit_encode_packed(vit_encoder_t* e, const float* pixels, const int3
       a.heads = d.H; a.dh = d.dh; a.dh_pad = d.dhp; a.ld_qkv = d.QKVN; a.ld_o = d.Op;
       a.reverse = reverse;
       reverse ^= 1;
-      ProfScope ps(e, s, VIT_PROF_ATTENTION);
+      ProfScope ps(e, s, VIT_PROF_ATTENTION, timing);
       HIP_TRY(d.bf16 ? launch_attention_bf16(a, s) : launch_attention_f32(a, s));
     }
     HIP_TRY(gemm(L.wo, o, d.Op, n_tok, EPI_BIAS_RESIDUAL, nullptr, d.D, x));
@@ -638,7 +710,7 @@ vit_status_t vit_encode_packed(vit_encoder_t* e, const float* pixels, const int3
     HIP_TRY(layernorm(e->lnf_g, e->lnf_b, d.final_ln, h, d.Dp, d.Dp));
     void* dst = d.proj_layers == 0 ? out_tokens : (void*)(ws + w.off_merge);
     const int dst_ld = d.proj_layers == 0 ? d.pin : d.pin_ld;
-    ProfScope ps(e, s, VIT_PROF_PATCHIFY);
+    ProfScope ps(e, s, VIT_PROF_PATCHIFY, timing);
     HIP_TRY(launch_token_merge(h, d.Dp, dst, dst_ld, (int)n_tiles, d.T, d.has_cls, d.g, d.merge, d.D, d.es, s));
   }
   if (d.proj_layers > 0) {
@@ -652,6 +724,25 @@ vit_status_t vit_encode_packed(vit_encoder_t* e, const float* pixels, const int3
     }
   }
   return VIT_OK;
+}
+
+vit_status_t vit_encode_packed(vit_encoder_t* e, const float* pixels, const int32_t* images_per_request,
+                               int32_t n_requests, const int32_t* tile_offsets, void* out_tokens,
+                               size_t out_capacity_bytes, int64_t* request_token_offsets, void* workspace,
+                               size_t workspace_bytes, void* stream) {
+  return encode_impl("vit_encode_packed", e, pixels, images_per_request, n_requests, tile_offsets, out_tokens,
+                     out_capacity_bytes, request_token_offsets, workspace, workspace_bytes, stream, false);
+}
+
+vit_status_t vit_encode_packed_static(vit_encoder_t* e, const float* pixels, const int32_t* images_per_request,
+                                      int32_t n_requests, const int32_t* tile_offsets, void* out_tokens,
+                                      size_t out_capacity_bytes, int64_t* request_token_offsets, void* stream) {
+  if (!e) return fail(VIT_EINVAL, "vit_encode_packed_static: NULL encoder");
+  if (!e->scratch)
+    return fail(VIT_EDEVICE, "vit_encode_packed_static: the static scratch array has no address on device %d: %s",
+                e->device, hipGetErrorString(e->scratch_error));
+  return encode_impl("vit_encode_packed_static", e, pixels, images_per_request, n_requests, tile_offsets, out_tokens,
+                     out_capacity_bytes, request_token_offsets, e->scratch, kStaticScratchBytes, stream, true);
 }
 
 vit_status_t vit_profile_enable(vit_encoder_t* e, int enable) {
