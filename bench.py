@@ -49,6 +49,24 @@ def flops(cfg, tile_offsets):
     return gemm + attn, gemm, attn
 
 
+def product_flops(cfg, tile_offsets):
+    """Algorithmic FLOPs of each matrix-product family of one step (keys as in VitEncoder.profile_read)."""
+    g = cfg["image_size"] // cfg["patch_size"]
+    P = g * g
+    T = P + cfg["has_cls"]
+    K = cfg["channels"] * cfg["patch_size"] ** 2
+    D, M, L = cfg["hidden"], cfg["mlp"], cfg["layers_local"] + cfg["layers_global"]
+    n_tiles = int(np.asarray(tile_offsets)[-1])
+    m = max(cfg["token_merge"], 1)
+    d_in, t_out, proj = D * m * m, (T if m == 1 else (g // m) ** 2), 0.0
+    for i in range(cfg["proj_layers"]):
+        proj += n_tiles * 2.0 * t_out * d_in * cfg["proj_dims"][i]
+        d_in = cfg["proj_dims"][i]
+    rows = float(n_tiles) * T
+    return {"gemm_patch": n_tiles * 2.0 * P * K * D, "gemm_qkv": L * 2.0 * rows * D * 3 * D, "gemm_out": L * 2.0 * rows * D * D,
+            "gemm_fc1": L * 2.0 * rows * D * M, "gemm_fc2": L * 2.0 * rows * D * M, "gemm_proj": proj}
+
+
 def cpu_baseline(cfg, weights, px, tile_offsets, n_sample):
     """Oracle (fp32, as it stands) on the first n_sample images of the batch; returns the JSON object."""
     from threadpoolctl import threadpool_info
@@ -316,6 +334,14 @@ def main():
             "avg_launch_ms": gemm_ms / max(gemm_n, 1), "flop_per_step": gemm_f,
         }
         result["kernel_ms_per_step"] = fam_ms
+        # every matrix product on a line of its own: launches and ms per step, ms per launch, TFLOP/s
+        pf = product_flops(cfg, to)
+        assert abs(sum(pf.values()) - gemm_f) <= 1e-9 * gemm_f
+        result["gemm_products"] = {
+            k: {"launches": int(prof[k][1] // args.steps), "ms_per_step": fam_ms[k],
+                "ms_per_launch": fam_ms[k] / max(prof[k][1] // args.steps, 1),
+                "tflops": pf[k] / (fam_ms[k] * 1e-3) / 1e12 if fam_ms[k] > 0 else None}
+            for k in pf}
         att_ms = fam_ms["attention"]
         result["attention_tflops"] = attn_f / (att_ms * 1e-3) / 1e12 if att_ms > 0 else None
         # LayerNorm passes: each reads fp32 [tokens, D] and writes the operand type
@@ -323,6 +349,15 @@ def main():
         ln_n = prof["layernorm"][1] // args.steps
         ln_bytes = ln_n * n_tiles * T * cfg["hidden"] * (4 + es)  # every encoder token, before any down-sampling
         result["layernorm_gbs"] = ln_bytes / (fam_ms["layernorm"] * 1e-3) / 1e9 if fam_ms["layernorm"] > 0 else None
+    if not args.no_kernel_events and cfg["dtype"] == "bf16":
+        # two more steps, outside the timed region, with the persistent kernel stamping its tiles: microseconds per tile
+        # in the k-loop and in the epilogue, and the shader clock the (power-limited) chip held, per matrix product
+        enc.profile_tiles_enable(True)
+        for _ in range(2):
+            enc.encode(px_dev, ipr, to, out=out)
+        result["tile_phases"] = {k: {"k_loop_us": v[0], "epilogue_us": v[1], "shader_clock_mhz": v[2], "tiles_stamped": int(v[3])}
+                                 for k, v in enc.profile_tiles_read().items()}
+        enc.profile_tiles_enable(False)
     enc.close()
     if args.cpu_sample > 0:
         result["cpu_baseline"] = cpu_baseline(cfg, weights, px, to, min(args.cpu_sample, n_images))

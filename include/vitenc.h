@@ -162,22 +162,44 @@ void vit_encoder_destroy(vit_encoder_t* enc);
 const char* vit_last_error(void);
 
 /*
- * Timing aid: average device time in milliseconds of each kernel family over all
- * vit_encode_packed calls since the last reset, measured with HIP events on the launch
- * stream.  Off by default (it adds events to the stream); enable != 0 switches it on and
- * resets the counters.  vit_profile_read synchronises the recorded events and fills
- * ms[VIT_PROF_COUNT] and launches[VIT_PROF_COUNT] with total milliseconds and number of
- * kernel launches per family.
+ * Timing aid: device time in milliseconds of each kernel family over all vit_encode_packed
+ * calls since the last reset, measured with HIP events on the launch stream.  Off by default
+ * (it adds events to the stream); enable != 0 switches it on and resets the counters.
+ * vit_profile_read synchronises the recorded events and fills ms[VIT_PROF_COUNT] and
+ * launches[VIT_PROF_COUNT] with total milliseconds and number of kernel launches per family.
+ * Every matrix product of the path has a family of its own.
  */
 enum {
-  VIT_PROF_PATCHIFY = 0, /* patch gather, CLS rows, token down-sampling */
-  VIT_PROF_GEMM = 1,     /* all matrix products incl. patch GEMM    */
+  VIT_PROF_PATCHIFY = 0,   /* patch gather, CLS rows, token down-sampling            */
+  VIT_PROF_GEMM_PATCH = 1, /* patch-embedding product (+bias +pos)                   */
   VIT_PROF_LAYERNORM = 2,
   VIT_PROF_ATTENTION = 3,
-  VIT_PROF_COUNT = 4
+  VIT_PROF_GEMM_QKV = 4,   /* h Wqkv^T + b                                           */
+  VIT_PROF_GEMM_OUT = 5,   /* attention output projection, + bias, added to x        */
+  VIT_PROF_GEMM_FC1 = 6,   /* first MLP product, + bias, GELU                        */
+  VIT_PROF_GEMM_FC2 = 7,   /* second MLP product, + bias, added to x                 */
+  VIT_PROF_GEMM_PROJ = 8,  /* projector layers                                       */
+  VIT_PROF_COUNT = 9
 };
 vit_status_t vit_profile_enable(vit_encoder_t* enc, int enable);
 vit_status_t vit_profile_read(vit_encoder_t* enc, double* ms, int64_t* launches);
+
+/*
+ * Measurement aid: where the persistent matrix-product kernel (the one that runs every large
+ * product) spends its time.  While enabled, each workgroup stamps the first 64 tiles it computes
+ * in every launch: a constant-rate device clock at the tile's start, after its k-loop and after
+ * its epilogue, and the shader clocks the tile took.  vit_profile_tiles_read fills, per family of
+ * VIT_PROF_* (arrays of VIT_PROF_COUNT; zero for families that ran no such kernel), the means
+ * over the stamped tiles of the LAST launch of that family: microseconds in the k-loop,
+ * microseconds in the epilogue, the shader clock in MHz (the chip is power-limited: this is what
+ * it held), and the number of tiles stamped.  Enabling allocates 4.5 MiB of pinned host memory
+ * (freed by disabling or by vit_encoder_destroy) and both calls synchronise the device; stamps
+ * are taken only by vit_encode_packed, not by vit_encode_packed_static.
+ * Errors: VIT_EINVAL (NULL, read while disabled), VIT_EDEVICE.
+ */
+vit_status_t vit_profile_tiles_enable(vit_encoder_t* enc, int enable);
+vit_status_t vit_profile_tiles_read(vit_encoder_t* enc, double* main_loop_us, double* epilogue_us,
+                                    double* clock_mhz, int64_t* tiles);
 
 /*
  * Pull-style hand-off of finished image tokens (paper Sec. 4.3, "Image Token Transfer": the

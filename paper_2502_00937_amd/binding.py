@@ -12,7 +12,9 @@ _LIB = None
 VIT_OK, VIT_EINVAL, VIT_ENOMEM, VIT_ECAPACITY, VIT_EDEVICE = 0, -1, -2, -3, -4
 VIT_DTYPE_FP32, VIT_DTYPE_BF16 = 0, 1
 VIT_STATIC_SCRATCH_BYTES, VIT_STATIC_MAX_IMAGES = 128 << 20, 256
-PROF_FAMILIES = ("patchify", "gemm", "layernorm", "attention")
+# order of include/vitenc.h's VIT_PROF_* enumerators
+PROF_FAMILIES = ("patchify", "gemm_patch", "layernorm", "attention", "gemm_qkv", "gemm_out", "gemm_fc1", "gemm_fc2",
+                 "gemm_proj")
 
 
 class VitError(RuntimeError):
@@ -63,6 +65,11 @@ def load_library():
     lib.vit_encoder_destroy.argtypes = [C.c_void_p]
     lib.vit_profile_enable.restype = C.c_int
     lib.vit_profile_enable.argtypes = [C.c_void_p, C.c_int]
+    lib.vit_profile_tiles_enable.restype = C.c_int
+    lib.vit_profile_tiles_enable.argtypes = [C.c_void_p, C.c_int]
+    lib.vit_profile_tiles_read.restype = C.c_int
+    lib.vit_profile_tiles_read.argtypes = [C.c_void_p, C.POINTER(C.c_double), C.POINTER(C.c_double),
+                                           C.POINTER(C.c_double), C.POINTER(C.c_int64)]
     lib.vit_handoff_create.restype = C.c_int
     lib.vit_handoff_create.argtypes = [C.c_int, C.POINTER(C.c_void_p)]
     lib.vit_handoff_destroy.restype = None
@@ -237,6 +244,18 @@ class TokenHandoff:
         _check(load_library().vit_handoff_release(self._h, request_id))
 
 
+def check_pixels(cfg: dict, pixels_shape, tile_offsets) -> None:
+    """The C ABI takes `pixels` as a bare pointer: the tile count it reads is tile_offsets[-1].  Refuse a tensor
+    that does not hold exactly that many [C, S, S] tiles before the library reads past it."""
+    to = np.asarray(tile_offsets)
+    want = (int(cfg["channels"]), int(cfg["image_size"]), int(cfg["image_size"]))
+    if len(pixels_shape) != 4 or tuple(int(v) for v in pixels_shape[1:]) != want:
+        raise VitError(VIT_EINVAL, f"pixels must be [n_tiles, {want[0]}, {want[1]}, {want[2]}], got {tuple(pixels_shape)}")
+    if to.size == 0 or int(to[-1]) != int(pixels_shape[0]):
+        raise VitError(VIT_EINVAL, f"tile_offsets ends at {int(to[-1]) if to.size else None} but pixels holds "
+                                   f"{int(pixels_shape[0])} tiles")
+
+
 # ---- convenience wrapper: torch tensors for device memory and the stream ----------------
 class VitEncoder:
     """Owns a handle; allocates output/workspace tensors with torch and passes raw pointers."""
@@ -275,6 +294,7 @@ class VitEncoder:
         """pixels: torch fp32 device tensor [n_tiles, C, S, S].  Returns (tokens, request_token_offsets)."""
         torch = self._torch
         assert pixels.is_cuda and pixels.dtype == torch.float32 and pixels.is_contiguous()
+        check_pixels(self.cfg, pixels.shape, tile_offsets)
         n_tiles = int(pixels.shape[0])
         n_images = int(np.asarray(tile_offsets).size - 1)
         n_tok, out_dim, out_bytes, ws_bytes = self.query(n_tiles, n_images)
@@ -293,7 +313,23 @@ class VitEncoder:
         _check(load_library().vit_profile_enable(self._handle, 1 if on else 0))
 
     def profile_read(self):
-        ms = (C.c_double * 4)()
-        n = (C.c_int64 * 4)()
+        """{family: (total ms, launches)}; "gemm" is the sum over the matrix-product families."""
+        k = len(PROF_FAMILIES)
+        ms = (C.c_double * k)()
+        n = (C.c_int64 * k)()
         _check(load_library().vit_profile_read(self._handle, ms, n))
-        return {PROF_FAMILIES[i]: (ms[i], n[i]) for i in range(4)}
+        prof = {PROF_FAMILIES[i]: (ms[i], n[i]) for i in range(k)}
+        products = [v for f, v in prof.items() if f.startswith("gemm_")]
+        prof["gemm"] = (sum(v[0] for v in products), sum(v[1] for v in products))
+        return prof
+
+    def profile_tiles_enable(self, on: bool = True):
+        _check(load_library().vit_profile_tiles_enable(self._handle, 1 if on else 0))
+
+    def profile_tiles_read(self):
+        """{family: (k-loop us per tile, epilogue us per tile, shader clock MHz, tiles stamped)} of each family's
+        last launch on the persistent matrix-product kernel."""
+        k = len(PROF_FAMILIES)
+        main, epi, mhz, n = (C.c_double * k)(), (C.c_double * k)(), (C.c_double * k)(), (C.c_int64 * k)()
+        _check(load_library().vit_profile_tiles_read(self._handle, main, epi, mhz, n))
+        return {PROF_FAMILIES[i]: (main[i], epi[i], mhz[i], n[i]) for i in range(k) if n[i] > 0}

@@ -120,6 +120,8 @@ struct GemmArgs {
   int cls;            // EPI_PATCH: 1 if a CLS row precedes the patches
   int epilogue;
   int reverse;        // 1: walk the row blocks from the last to the first (see vit_encode_packed)
+  unsigned long long* tile_stamps;  // measurement aid, normally null: [256 workgroups][kTileStampSlots][4] words written
+                                    // by the persistent kernel per tile (see vit_profile_tiles_read)
   int stream_out;     // 1: the bf16 output exceeds the memory-side cache; the persistent kernel stores it non-temporally
 };
 
@@ -140,6 +142,8 @@ __device__ __forceinline__ void epilogue_store(const GemmArgs& a, int row, int c
     a.resid[((size_t)tile * a.tokens + tok) * a.ldo + col] = v + a.pos[(size_t)tok * a.ldo + col];
   }
 }
+
+constexpr int kTileStampSlots = 64;  // tiles per workgroup whose phases are recorded
 
 // Attention work item: one block of query rows inside one segment.
 struct AttnWork {

@@ -166,6 +166,9 @@ constexpr int D_STAGE_BYTES = (D_BM + D_BN) * D_ROW;  // 64 KiB
 constexpr int D_STAGING_ROW = 144, D_STAGING_BYTES = 8 * 16 * D_STAGING_ROW;
 constexpr int D_LDS_BYTES = D_ST * D_STAGE_BYTES + D_STAGING_BYTES;  // 146 KiB of the 160 KiB
 constexpr int D_GROUP_M = 8, D_GROUP_N = 4;
+#ifndef VIT_RESID_PD
+#define VIT_RESID_PD 4
+#endif
 constexpr int D_LOADS = 8;  // direct-to-LDS instructions per wave and stage (4 for A, 4 for W), 8 rows each
 
 typedef const __attribute__((address_space(1))) void* gptr_t;
@@ -173,11 +176,18 @@ typedef __attribute__((address_space(3))) void* lptr_t;
 
 // Epilogue of one wave of the persistent kernel: same register layout as wave_epilogue, but staged
 // 16 rows at a time through the wave's private 16 x 144-byte LDS rows (`st`).
-template <int EPI, bool STREAM_OUT>
-__device__ __forceinline__ void wave_epilogue_p(const GemmArgs& a, f32x16 (&acc)[4][2], const f32x4 (&bias)[2][4],
-                                                unsigned char* st, int row0, int ncol0, int lane) {
+template <int EPI, bool STREAM_OUT, bool FULL>
+__device__ __forceinline__ void wave_epilogue_p(const GemmArgs& a, f32x16 (&acc)[4][2], unsigned char* st, int row0,
+                                                int ncol0, int lane) {
   constexpr int FM = 4, FN = 2;
   const int lrow = lane & 31, lk = lane >> 5;
+  f32x4 bias[FN][4];  // per accumulator quad (the residual path adds its bias after the LDS round trip instead)
+  if constexpr (EPI != EPI_BIAS_RESIDUAL) {
+#pragma unroll
+    for (int j = 0; j < FN; ++j)
+#pragma unroll
+      for (int jj = 0; jj < 4; ++jj) bias[j][jj] = *(const f32x4*)(a.bias + ncol0 + j * 32 + jj * 8 + lk * 4);
+  }
 
   if constexpr (EPI == EPI_PATCH) {
 #pragma unroll
@@ -203,10 +213,13 @@ __device__ __forceinline__ void wave_epilogue_p(const GemmArgs& a, f32x16 (&acc)
     }
   } else if constexpr (EPI == EPI_BIAS_RESIDUAL) {
     // Pieces of 16 rows x 32 fp32 columns (128 bytes + pad per staged row); a piece is read back
-    // as 8 lanes per row, 8 rows per pass.  The residual values of a 32 x 32 unit (2 pieces of
-    // 2 passes) are loaded one unit ahead so their latency hides behind the previous unit.
-    // Addresses are a wave-uniform base (scalar arithmetic) plus a per-lane byte offset that never
-    // changes; the bounds tests compare a per-lane limit with a compile-time row / column.
+    // as 8 lanes per row, 8 rows per pass, and the bias is added there (one float4 per lane and column
+    // block instead of one per accumulator quad).  The residual values of a 32 x 32 unit are loaded one
+    // unit ahead; two, three and up to five units ahead (the registers of the next tile's first fragments
+    // are free here, see the kernel) measured the same or slower: the epilogue is not bound by the latency
+    // of these loads.  Addresses are a wave-uniform base (scalar arithmetic) plus a per-lane byte offset
+    // that never changes; FULL tiles (all but the last row block and a ragged last column) carry no bounds
+    // test.
     const int sr0 = lane >> 3, sc = (lane & 7) * 4;
     const uint32_t lane_off = (uint32_t)(sr0 * a.ldo + sc) * 4u;
     unsigned char* const tile_base = (unsigned char*)a.resid + ((size_t)row0 * a.ldo + ncol0) * 4;
@@ -214,8 +227,13 @@ __device__ __forceinline__ void wave_epilogue_p(const GemmArgs& a, f32x16 (&acc)
     auto x_ptr = [&](int i, int j, int half, int p) {
       return (float*)(tile_base + ((size_t)(i * 32 + half * 16 + p * 8) * a.ldo + j * 32) * 4 + lane_off);
     };
-    auto x_ok = [&](int i, int j, int half, int p) { return i * 32 + half * 16 + p * 8 < row_lim && j * 32 < col_lim; };
-    f32x4 xin[2][2][2];  // [buffer][half][pass] of one (row block, column block) unit
+    auto x_ok = [&](int i, int j, int half, int p) {
+      return FULL || (i * 32 + half * 16 + p * 8 < row_lim && j * 32 < col_lim);
+    };
+    f32x4 brow[FN];
+#pragma unroll
+    for (int j = 0; j < FN; ++j) brow[j] = *(const f32x4*)(a.bias + ncol0 + j * 32 + sc);
+    f32x4 xin[2][2][2];  // [buffer][half][pass] of one unit
     auto load_unit = [&](int u, int buf) {  // unit u = i * FN + j
       const int i = u / FN, j = u % FN;
 #pragma unroll
@@ -229,23 +247,20 @@ __device__ __forceinline__ void wave_epilogue_p(const GemmArgs& a, f32x16 (&acc)
     for (int u = 0; u < FM * FN; ++u) {
       const int i = u / FN, j = u % FN;
       if (u + 1 < FM * FN) load_unit(u + 1, (u + 1) & 1);
-      f32x4 v[4];
-#pragma unroll
-      for (int jj = 0; jj < 4; ++jj)
-#pragma unroll
-        for (int e = 0; e < 4; ++e) v[jj][e] = acc[i][j][jj * 4 + e] + bias[j][jj][e];
 #pragma unroll
       for (int half = 0; half < 2; ++half) {
         if ((lrow >> 4) == half) {
 #pragma unroll
-          for (int jj = 0; jj < 4; ++jj)
-            *(f32x4*)(st + (lrow & 15) * D_STAGING_ROW + (jj * 8 + lk * 4) * 4) = v[jj];
+          for (int jj = 0; jj < 4; ++jj) {
+            const f32x4 v = {acc[i][j][jj * 4], acc[i][j][jj * 4 + 1], acc[i][j][jj * 4 + 2], acc[i][j][jj * 4 + 3]};
+            *(f32x4*)(st + (lrow & 15) * D_STAGING_ROW + (jj * 8 + lk * 4) * 4) = v;
+          }
         }
         __builtin_amdgcn_wave_barrier();
 #pragma unroll
         for (int p = 0; p < 2; ++p) {
           const f32x4 t = *(const f32x4*)(st + (p * 8 + sr0) * D_STAGING_ROW + sc * 4);
-          if (x_ok(i, j, half, p)) *(f32x4*)x_ptr(i, j, half, p) = xin[u & 1][half][p] + t;
+          if (x_ok(i, j, half, p)) *(f32x4*)x_ptr(i, j, half, p) = xin[u & 1][half][p] + (t + brow[j]);
         }
         __builtin_amdgcn_wave_barrier();
       }
@@ -287,7 +302,7 @@ __device__ __forceinline__ void wave_epilogue_p(const GemmArgs& a, f32x16 (&acc)
         for (int p = 0; p < 2; ++p) {  // 8 lanes per row (8 bf16 each), 8 rows per pass
           const int sr = p * 8 + (lane >> 3);
           const u32x4 t = *(const u32x4*)(st + sr * D_STAGING_ROW + sc * 2);
-          if (i * 32 + half * 16 + p * 8 < row_lim && col_ok) {
+          if (FULL || (i * 32 + half * 16 + p * 8 < row_lim && col_ok)) {
             u32x4* dst = (u32x4*)(tile_base + (size_t)(i * 32 + half * 16 + p * 8) * a.ldo * 2 + lane_off);
             // STREAM_OUT: the output is larger than the memory-side cache; it passes through once and
             // would only displace the operands, so it is stored non-temporally (-1 % on the large encode
@@ -449,7 +464,9 @@ __global__ __launch_bounds__(512) void gemm_bf16_dma_kernel(const GemmArgs a, in
   //                   pair; the other four follow in sub-step 0 of the next stage (eight in a row
   //                   would queue up in the memory pipeline and hold back the MFMAs behind them).
   bool pend = false;  // the second half of a stage's loads is still to be issued
-  auto k_stage = [&](auto load_tag, auto next_tag) {
+  // AHEAD = false (a tile's last stage in the residual kernel): the next tile's first fragments are not read
+  // here but after the epilogue, which needs their registers for residual values in flight.
+  auto k_stage = [&](auto load_tag, auto next_tag, const bool AHEAD) {
     constexpr bool LOAD = decltype(load_tag)::value, NEXT = decltype(next_tag)::value;
     const int sn = st_c ^ 1;
     sub_step(st_c, 1, fa0, fb0, fa1, fb1, pend, 4);
@@ -465,12 +482,12 @@ __global__ __launch_bounds__(512) void gemm_bf16_dma_kernel(const GemmArgs a, in
     __builtin_amdgcn_sched_barrier(0);
     if (NEXT) sync_stage();
     __builtin_amdgcn_sched_barrier(0);
-    if (NEXT) { fb0[0] = rd_b(sn, 0, 0); fb0[1] = rd_b(sn, 0, 1); fa0[0] = rd_a(sn, 0, 0); }
+    if (NEXT && AHEAD) { fb0[0] = rd_b(sn, 0, 0); fb0[1] = rd_b(sn, 0, 1); fa0[0] = rd_a(sn, 0, 0); }
     __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
     for (int i = 0; i < FM; ++i) {
       mm(i, fa1[i], fb1);
-      if (NEXT && i < FM - 1) fa0[i + 1] = rd_a(sn, 0, i + 1);
+      if (NEXT && AHEAD && i < FM - 1) fa0[i + 1] = rd_a(sn, 0, i + 1);
       if (LOAD) issue_load(st_c, i);
       __builtin_amdgcn_sched_barrier(0);
     }
@@ -493,9 +510,14 @@ __global__ __launch_bounds__(512) void gemm_bf16_dma_kernel(const GemmArgs a, in
     for (int i = 0; i < FM; ++i) fa0[i] = rd_a(0, 0, i);
   }
 
+  int stamp_i = 0;  // measurement aid: tiles of this workgroup stamped so far
   for (int g_c = next_group(xcd); g_c < n_groups; g_c = next_group(g_c + 8)) {
     int tm, tn;
     tile_of(g_c, tm, tn);
+    // measurement aid (off unless the host asked for it): constant-rate clock at the tile's start, after its
+    // k-loop and after its epilogue, and the shader clocks the tile took
+    unsigned long long stamp_t0 = 0, stamp_t1 = 0, stamp_c0 = 0;
+    if (a.tile_stamps) { stamp_t0 = wall_clock64(); stamp_c0 = __builtin_readcyclecounter(); }
     const int row0 = tm * D_BM + wm * TM, ncol0 = tn * D_BN + wn * TN;
 #pragma unroll
     for (int i = 0; i < FM; ++i)
@@ -507,16 +529,43 @@ __global__ __launch_bounds__(512) void gemm_bf16_dma_kernel(const GemmArgs a, in
     // ahead; then the very last stage of the list, which has nothing after it
     const int n_ld = min(KT, total_stages - issued);
     const int n_nx = min(KT, total_stages - 1 - consumed);
-    for (int kt = 0; kt < n_ld; ++kt) k_stage(std::true_type{}, std::true_type{});
-    for (int kt = n_ld; kt < n_nx; ++kt) k_stage(std::false_type{}, std::true_type{});
-    for (int kt = max(n_ld, n_nx); kt < KT; ++kt) k_stage(std::false_type{}, std::false_type{});
+    constexpr bool RESID = EPI == EPI_BIAS_RESIDUAL;
+    const std::true_type T{};
+    const std::false_type F{};
+    // (wave-uniform run-time flag: a compile-time variant of the last stage would merge three copies of the
+    //  accumulators' live ranges and spill)
+    for (int kt = 0; kt < n_ld; ++kt) k_stage(T, T, !RESID || kt != KT - 1);
+    for (int kt = n_ld; kt < n_nx; ++kt) k_stage(F, T, !RESID || kt != KT - 1);
+    for (int kt = max(n_ld, n_nx); kt < KT; ++kt) k_stage(F, F, true);
+    if constexpr (RESID) {  // the fragment registers are dead across the epilogue: say so
+#pragma unroll
+      for (int i = 0; i < FM; ++i) fa0[i] = bf16x8{};
+      fb0[0] = bf16x8{}; fb0[1] = bf16x8{};
+    }
     asm volatile("" ::: "memory");  // keep the epilogue's loads below the k-loop
-    f32x4 bias[FN][4];
+    if (a.tile_stamps) stamp_t1 = wall_clock64();
+    // a wave's 128 x 64 block lies wholly inside the matrix for all but the last row block / a ragged last column
+    if (row0 + TM <= a.M && ncol0 + TN <= a.N)
+      wave_epilogue_p<EPI, STREAM_OUT, true>(a, acc, staging + wave * 16 * D_STAGING_ROW, row0, ncol0, lane);
+    else
+      wave_epilogue_p<EPI, STREAM_OUT, false>(a, acc, staging + wave * 16 * D_STAGING_ROW, row0, ncol0, lane);
+    if constexpr (RESID) {  // the next tile's first fragments (its first stage landed before the last sync)
+      if (consumed < total_stages) {
+        fb0[0] = rd_b(st_c, 0, 0); fb0[1] = rd_b(st_c, 0, 1);
 #pragma unroll
-    for (int j = 0; j < FN; ++j)
-#pragma unroll
-      for (int jj = 0; jj < 4; ++jj) bias[j][jj] = *(const f32x4*)(a.bias + ncol0 + j * 32 + jj * 8 + lk * 4);
-    wave_epilogue_p<EPI, STREAM_OUT>(a, acc, bias, staging + wave * 16 * D_STAGING_ROW, row0, ncol0, lane);
+        for (int i = 0; i < FM; ++i) fa0[i] = rd_a(st_c, 0, i);
+      }
+    }
+    if (a.tile_stamps) {
+      asm volatile("" ::: "memory");
+      const unsigned long long stamp_t2 = wall_clock64();
+      if (tid == 0 && stamp_i < kTileStampSlots) {
+        unsigned long long* d = a.tile_stamps + ((size_t)blockIdx.x * kTileStampSlots + stamp_i) * 4;
+        d[0] = stamp_t0; d[1] = stamp_t1; d[2] = stamp_t2;
+        d[3] = __builtin_readcyclecounter() - stamp_c0 + 1;  // never 0: marks the slot as written
+      }
+      ++stamp_i;
+    }
   }
 }
 
@@ -707,9 +756,10 @@ hipError_t launch_dma(const GemmArgs& a, hipStream_t s) {
     if (hipError_t e = hipDeviceGetAttribute(&n_cu, hipDeviceAttributeMultiprocessorCount, dev); e != hipSuccess) return e;
     cu_of_device[dev].store(n_cu, std::memory_order_relaxed);
   }
-  // one workgroup per compute unit: 8 XCDs x 32 slots (slots beyond the unit count of an XCD stay off)
+  // one workgroup per compute unit: 8 XCDs x 32 slots.  The unit count is a performance assumption only (the
+  // workgroups never wait for each other); a device with fewer units takes the small-tile kernel instead.
   const int grid = 8 * D_GROUP_M * D_GROUP_N;
-  if (n_cu < grid) return hipErrorInvalidValue;
+  if (n_cu < grid) return launch_ring(a, s);
 #define VIT_LAUNCH(EPI, STREAM)                                                                                      \
   do {                                                                                                               \
     auto kfn = gemm_bf16_dma_kernel<EPI, STREAM>;                                                                    \

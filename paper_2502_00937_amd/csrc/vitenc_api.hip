@@ -169,6 +169,8 @@ struct StageSlot {
 
 struct ProfRec { int family; hipEvent_t start, stop; };
 
+constexpr size_t kStampWordsPerFamily = (size_t)256 * kTileStampSlots * 4;
+
 }  // namespace
 
 struct vit_encoder {
@@ -179,6 +181,7 @@ struct vit_encoder {
   size_t dev_weight_bytes = 0;
   unsigned char* scratch = nullptr;  // this device's copy of the static scratch array (vit_encode_packed_static)
   hipError_t scratch_error = hipSuccess;
+  unsigned long long* tile_stamps = nullptr;  // pinned [VIT_PROF_COUNT][256][kTileStampSlots][4], vit_profile_tiles_*
   Linear patch, proj[2];
   const float *cls = nullptr, *pos = nullptr, *lnf_g = nullptr, *lnf_b = nullptr;
   std::vector<Layer> layers;
@@ -187,8 +190,8 @@ struct vit_encoder {
   bool profiling = false;
   std::vector<ProfRec> prof;
   std::vector<hipEvent_t> free_events;
-  double prof_ms[VIT_PROF_COUNT] = {0, 0, 0, 0};
-  int64_t prof_n[VIT_PROF_COUNT] = {0, 0, 0, 0};
+  double prof_ms[VIT_PROF_COUNT] = {};
+  int64_t prof_n[VIT_PROF_COUNT] = {};
 };
 
 namespace {
@@ -471,6 +474,7 @@ vit_status_t vit_encoder_create(const vit_config_t* cfg, const float* weights, s
 void vit_encoder_destroy(vit_encoder_t* e) {
   if (!e) return;
   (void)hipSetDevice(e->device);
+  if (e->tile_stamps) (void)hipHostFree(e->tile_stamps);
   for (auto& r : e->prof) { (void)hipEventDestroy(r.start); (void)hipEventDestroy(r.stop); }
   for (auto ev : e->free_events) (void)hipEventDestroy(ev);
   for (auto& s : e->stage) {
@@ -645,7 +649,8 @@ static vit_status_t encode_impl(const char* fn, vit_encoder_t* e, const float* p
   // Every kernel of the chain walks the token rows in the direction opposite to its producer:
   // what a kernel wrote last is still in the 256 MB memory-side cache when its consumer starts there.
   int reverse = 0;
-  auto gemm = [&](const Linear& lin, const void* A, int lda, int M, int epi, void* out, int ldo, float* resid) -> hipError_t {
+  auto gemm = [&](int family, const Linear& lin, const void* A, int lda, int M, int epi, void* out, int ldo,
+                  float* resid) -> hipError_t {
     GemmArgs a;
     memset(&a, 0, sizeof(a));
     a.A = A; a.W = lin.W; a.bias = lin.bias; a.out = out; a.resid = resid; a.pos = e->pos;
@@ -654,7 +659,8 @@ static vit_status_t encode_impl(const char* fn, vit_encoder_t* e, const float* p
     a.reverse = reverse;
     reverse ^= 1;
     a.stream_out = (size_t)M * lin.N * d.es > kCacheBytes;
-    ProfScope ps(e, s, VIT_PROF_GEMM, timing);
+    a.tile_stamps = e->tile_stamps && timing ? e->tile_stamps + (size_t)family * kStampWordsPerFamily : nullptr;
+    ProfScope ps(e, s, family, timing);
     return d.bf16 ? launch_gemm_bf16(a, s) : launch_gemm_f32(a, s);
   };
   auto layernorm = [&](const float* g_, const float* b_, int normalize, void* out, int ldo, int out_cols) -> hipError_t {
@@ -671,14 +677,14 @@ static vit_status_t encode_impl(const char* fn, vit_encoder_t* e, const float* p
     HIP_TRY(launch_patch_gather(pixels, u, d.Kp_pad, (int)n_tiles, d.C, d.S, d.p, d.g, d.Kp_pad, d.bf16, s));
     if (d.has_cls) HIP_TRY(launch_cls_rows(x, d.D, e->cls, e->pos, (int)n_tiles, d.T, d.D, s));
   }
-  HIP_TRY(gemm(e->patch, u, d.Kp_pad, (int)(n_tiles * d.P), EPI_PATCH, nullptr, d.D, x));
+  HIP_TRY(gemm(VIT_PROF_GEMM_PATCH, e->patch, u, d.Kp_pad, (int)(n_tiles * d.P), EPI_PATCH, nullptr, d.D, x));
   if (d.Op > d.H * d.dhp) HIP_TRY(launch_fill_zero_cols(o, d.Op, n_tok, d.H * d.dhp, d.Op, d.es, s));
 
   // ---- transformer blocks
   for (int l = 0; l < d.L; ++l) {
     const Layer& L = e->layers[l];
     HIP_TRY(layernorm(L.ln1_g, L.ln1_b, 1, h, d.Dp, d.Dp));
-    HIP_TRY(gemm(L.qkv, h, d.Dp, n_tok, EPI_BIAS, qkv, d.QKVN, nullptr));
+    HIP_TRY(gemm(VIT_PROF_GEMM_QKV, L.qkv, h, d.Dp, n_tok, EPI_BIAS, qkv, d.QKVN, nullptr));
     {
       const bool global = l >= d.L_loc;
       AttnArgs a;
@@ -691,10 +697,10 @@ static vit_status_t encode_impl(const char* fn, vit_encoder_t* e, const float* p
       ProfScope ps(e, s, VIT_PROF_ATTENTION, timing);
       HIP_TRY(d.bf16 ? launch_attention_bf16(a, s) : launch_attention_f32(a, s));
     }
-    HIP_TRY(gemm(L.wo, o, d.Op, n_tok, EPI_BIAS_RESIDUAL, nullptr, d.D, x));
+    HIP_TRY(gemm(VIT_PROF_GEMM_OUT, L.wo, o, d.Op, n_tok, EPI_BIAS_RESIDUAL, nullptr, d.D, x));
     HIP_TRY(layernorm(L.ln2_g, L.ln2_b, 1, h, d.Dp, d.Dp));
-    HIP_TRY(gemm(L.w1, h, d.Dp, n_tok, EPI_BIAS_GELU, u, d.Mp, nullptr));
-    HIP_TRY(gemm(L.w2, u, d.Mp, n_tok, EPI_BIAS_RESIDUAL, nullptr, d.D, x));
+    HIP_TRY(gemm(VIT_PROF_GEMM_FC1, L.w1, h, d.Dp, n_tok, EPI_BIAS_GELU, u, d.Mp, nullptr));
+    HIP_TRY(gemm(VIT_PROF_GEMM_FC2, L.w2, u, d.Mp, n_tok, EPI_BIAS_RESIDUAL, nullptr, d.D, x));
   }
 
   // ---- final LayerNorm, token down-sampling and projector
@@ -717,10 +723,10 @@ static vit_status_t encode_impl(const char* fn, vit_encoder_t* e, const float* p
     const void* pin = d.merge == 1 ? h : (const void*)(ws + w.off_merge);
     const int n_out = (int)w.n_out;
     if (d.proj_layers == 1) {
-      HIP_TRY(gemm(e->proj[0], pin, d.pin_ld, n_out, EPI_BIAS, out_tokens, d.out_dim, nullptr));
+      HIP_TRY(gemm(VIT_PROF_GEMM_PROJ, e->proj[0], pin, d.pin_ld, n_out, EPI_BIAS, out_tokens, d.out_dim, nullptr));
     } else {
-      HIP_TRY(gemm(e->proj[0], pin, d.pin_ld, n_out, EPI_BIAS_GELU, u, d.proj0_ld, nullptr));
-      HIP_TRY(gemm(e->proj[1], u, d.proj0_ld, n_out, EPI_BIAS, out_tokens, d.out_dim, nullptr));
+      HIP_TRY(gemm(VIT_PROF_GEMM_PROJ, e->proj[0], pin, d.pin_ld, n_out, EPI_BIAS_GELU, u, d.proj0_ld, nullptr));
+      HIP_TRY(gemm(VIT_PROF_GEMM_PROJ, e->proj[1], u, d.proj0_ld, n_out, EPI_BIAS, out_tokens, d.out_dim, nullptr));
     }
   }
   return VIT_OK;
@@ -783,6 +789,52 @@ vit_status_t vit_profile_read(vit_encoder_t* e, double* ms, int64_t* launches) {
   }
   e->prof.clear();
   for (int i = 0; i < VIT_PROF_COUNT; ++i) { ms[i] = e->prof_ms[i]; launches[i] = e->prof_n[i]; }
+  return VIT_OK;
+}
+
+vit_status_t vit_profile_tiles_enable(vit_encoder_t* e, int enable) {
+  if (!e) return fail(VIT_EINVAL, "vit_profile_tiles_enable: NULL encoder");
+  HIP_TRY(hipSetDevice(e->device));
+  HIP_TRY(hipDeviceSynchronize());  // no kernel may still be writing stamps
+  const size_t bytes = (size_t)VIT_PROF_COUNT * kStampWordsPerFamily * sizeof(unsigned long long);
+  if (enable) {
+    if (!e->tile_stamps) HIP_TRY(hipHostMalloc((void**)&e->tile_stamps, bytes, hipHostMallocDefault));
+    memset(e->tile_stamps, 0, bytes);
+  } else if (e->tile_stamps) {
+    HIP_TRY(hipHostFree(e->tile_stamps));
+    e->tile_stamps = nullptr;
+  }
+  return VIT_OK;
+}
+
+vit_status_t vit_profile_tiles_read(vit_encoder_t* e, double* main_loop_us, double* epilogue_us, double* clock_mhz,
+                                    int64_t* tiles) {
+  if (!e || !main_loop_us || !epilogue_us || !clock_mhz || !tiles)
+    return fail(VIT_EINVAL, "vit_profile_tiles_read: NULL argument");
+  if (!e->tile_stamps) return fail(VIT_EINVAL, "vit_profile_tiles_read: not enabled");
+  HIP_TRY(hipSetDevice(e->device));
+  HIP_TRY(hipDeviceSynchronize());
+  int rate_khz = 0;  // of the constant-rate clock the kernel reads
+  HIP_TRY(hipDeviceGetAttribute(&rate_khz, hipDeviceAttributeWallClockRate, e->device));
+  if (rate_khz <= 0) return fail(VIT_EDEVICE, "vit_profile_tiles_read: the device reports no wall-clock rate");
+  const double us_per_tick = 1e3 / (double)rate_khz;
+  for (int f = 0; f < VIT_PROF_COUNT; ++f) {
+    const unsigned long long* D = e->tile_stamps + (size_t)f * kStampWordsPerFamily;
+    double main_t = 0, epi_t = 0, cycles = 0;
+    int64_t n = 0;
+    for (size_t r = 0; r < (size_t)256 * kTileStampSlots; ++r) {
+      const unsigned long long* d = D + r * 4;
+      if (!d[3]) continue;
+      main_t += (double)(d[1] - d[0]);
+      epi_t += (double)(d[2] - d[1]);
+      cycles += (double)(d[3] - 1);
+      ++n;
+    }
+    tiles[f] = n;
+    main_loop_us[f] = n ? main_t / n * us_per_tick : 0.0;
+    epilogue_us[f] = n ? epi_t / n * us_per_tick : 0.0;
+    clock_mhz[f] = main_t + epi_t > 0 ? cycles / ((main_t + epi_t) * us_per_tick) : 0.0;
+  }
   return VIT_OK;
 }
 

@@ -417,6 +417,44 @@ def test_random_small_encoders_match_oracle(seed):
     check_case(cfg, tpi, ipr, wseed=seed, pseed=seed + 50, label=f"random{seed}")
 
 
+def _plain_cfg(**kw):
+    cfg = {"image_size": 42, "patch_size": 14, "channels": 3, "hidden": 64, "heads": 1, "mlp": 128, "layers_local": 1,
+           "layers_global": 1, "has_cls": 1, "final_ln": 1, "ln_eps": 1e-6, "proj_layers": 1, "proj_dims": (48,),
+           "dtype": "bf16", "token_merge": 1}
+    cfg.update(kw)
+    return cfg
+
+
+@pytest.mark.parametrize("dh,heads,dtype", [(8, 4, "bf16"), (16, 3, "bf16"), (32, 2, "bf16"), (40, 2, "bf16"), (56, 1, "bf16"),
+                                            (88, 2, "bf16"), (104, 1, "bf16"), (112, 2, "bf16"), (120, 1, "bf16"),
+                                            (8, 2, "fp32"), (40, 2, "fp32"), (88, 1, "fp32"), (120, 1, "fp32")])
+def test_every_accepted_head_dim_matches_oracle(dh, heads, dtype):
+    """Head dims that are stored padded (to 64, 96 or 128 columns per head, zero weight rows) with the true head
+    dim in the logit scale: every multiple of 8 the library accepts that the presets and the random cases leave out."""
+    cfg = _plain_cfg(hidden=dh * heads, heads=heads, mlp=8 * (dh // 8 + 5), dtype=dtype)
+    say(f"case head dim {dh} x {heads} heads, {dtype}")
+    check_case(cfg, [2, 1, 3], [1, 0, 2], wseed=dh, pseed=dh + 1, label=f"dh{dh}")
+
+
+@pytest.mark.parametrize("channels,dtype", [(1, "bf16"), (4, "bf16"), (1, "fp32"), (4, "fp32"), (16, "bf16")])
+def test_channel_counts_other_than_three(channels, dtype):
+    """Patch vectors of C p^2 values for C = 1, 4 and the maximum, 16 (the patch product's contraction length
+    196, 784, 3136 before padding)."""
+    cfg = _plain_cfg(channels=channels, dtype=dtype, hidden=128, heads=2)
+    say(f"case {channels} channels, {dtype}")
+    check_case(cfg, [1, 2], [2], wseed=channels, pseed=7, label=f"C{channels}")
+
+
+@pytest.mark.parametrize("has_cls,dtype", [(0, "bf16"), (1, "bf16"), (0, "fp32"), (1, "fp32")])
+def test_one_patch_tiles(has_cls, dtype):
+    """Tiles of a single patch (image side = patch side): one token per tile, or two with the CLS row; local
+    attention over one or two keys, global attention over the few tokens of an image."""
+    cfg = _plain_cfg(image_size=14, has_cls=has_cls, dtype=dtype, hidden=128, heads=2, layers_local=2)
+    assert gen.tokens_per_tile(cfg) == 1 + has_cls
+    say(f"case one-patch tiles, has_cls={has_cls}, {dtype}")
+    check_case(cfg, [1, 3, 1, 2], [2, 0, 2], wseed=11, pseed=12, label=f"one-patch cls{has_cls}")
+
+
 def test_attention_logits_that_outgrow_the_reference_maximum():
     """Logits that rise by far more than 2^64 (as exp2 arguments) from the first keys of a segment to its last:
     every query is -64 e_0, key t carries 8 cos(pi t / 256) in channel 0 (a position table on a circle, which

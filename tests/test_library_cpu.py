@@ -145,6 +145,23 @@ def test_create_rejects_null_and_bad_arguments_without_a_device():
     lib.vit_encoder_destroy(None)  # NULL-safe
 
 
+def test_binding_refuses_pixels_that_do_not_match_the_tile_offsets():
+    """The C ABI has no pixel capacity argument; the binding checks the tensor's shape against the config and
+    against tile_offsets[-1] before anything is launched."""
+    cfg = gen.get_config("test_small_bf16")
+    S, Cn = cfg["image_size"], cfg["channels"]
+    B.check_pixels(cfg, (3, Cn, S, S), [0, 1, 3])
+    for shape, to in [((3, Cn, S, S), [0, 1, 4]),          # more tiles announced than the tensor holds
+                      ((3, Cn, S, S), [0, 1, 2]),          # fewer
+                      ((3, Cn, S + 1, S), [0, 1, 3]),      # wrong tile size
+                      ((3, Cn + 1, S, S), [0, 1, 3]),      # wrong channel count
+                      ((3 * Cn * S * S,), [0, 1, 3]),      # flat
+                      ((3, Cn, S, S), [])]:
+        with pytest.raises(V.VitError) as e:
+            B.check_pixels(cfg, shape, to)
+        assert e.value.status == B.VIT_EINVAL
+
+
 def test_no_cpu_fallback():
     import torch
 
