@@ -37,14 +37,18 @@ constexpr float REFERENCE_LIMIT = 18446744073709551616.0f;  // 2^64: a row sum t
 // QB = 32-query blocks per wave, NW = waves per workgroup: a work item is 32 * QB * NW query rows.
 // All head dims run QB = 1, NW = 4 (128 rows); QB = 2 (each K / V^T fragment feeding two MFMAs, two
 // waves per SIMD) was measured 15 % slower.
+// DHP = head dim as stored (a multiple of 8: 64, 72, 80, 96, 128).  The S^T product runs over DHL = DHP rounded up
+// to whole 16-wide k-steps: for 72 the K tile's LDS rows carry 8 zero columns (written once, never by the loader)
+// and the Q fragment of the last half k-step is zero, so nothing is padded in HBM.
 template <int DHP, int QB, int NW>
 struct AttnShape {
+  static constexpr int DHL = (DHP + 15) / 16 * 16;  // head dim of the K rows in LDS
   static constexpr int ANT = 64 * NW;            // threads per workgroup
   static constexpr int AQ = 32 * QB * NW;        // query rows per work item
-  static constexpr int KS = DHP / 16;            // k-steps of the S^T product
+  static constexpr int KS = DHL / 16;            // k-steps of the S^T product
   static constexpr int DB = (DHP + 31) / 32;     // 32-row blocks of O^T
   static constexpr int NCH = DHP / 8;            // 16-byte chunks per K/V row
-  static constexpr int K_STRIDE = DHP * 2 + 16;  // bytes per K row in LDS (padding kills bank conflicts)
+  static constexpr int K_STRIDE = DHL * 2 + 16;  // bytes per K row in LDS (padding kills bank conflicts)
   static constexpr int VT_STRIDE = AKV * 2 + 8;  // bytes per V^T row in LDS
   static constexpr int K_BYTES = AKV * K_STRIDE;
   static constexpr int VT_BYTES = DB * 32 * VT_STRIDE;
@@ -82,8 +86,15 @@ __global__ __launch_bounds__(64 * NW, QB == 1 ? (DHP == 64 ? 4 : DHP <= 96 ? 3 :
   for (int qb = 0; qb < QB; ++qb) {
     const int qload = min(w.q0 + (wave * QB + qb) * 32 + lq, seg_end - 1);
 #pragma unroll
-    for (int ks = 0; ks < Sh::KS; ++ks)
-      qf[qb][ks] = *(const bf16x8*)(base + (size_t)qload * a.ld_qkv + qoff + ks * 16 + g * 8);
+    for (int ks = 0; ks < Sh::KS; ++ks) {
+      if (ks * 16 + 8 < DHP) {  // both 8-wide halves of the k-step lie inside the head
+        qf[qb][ks] = *(const bf16x8*)(base + (size_t)qload * a.ld_qkv + qoff + ks * 16 + g * 8);
+      } else {  // head dim 72: the upper half of the last k-step does not exist; its lanes feed zeros
+        const bf16x8 lo = *(const bf16x8*)(base + (size_t)qload * a.ld_qkv + qoff + ks * 16);
+        const u32x4 z = {0u, 0u, 0u, 0u};
+        qf[qb][ks] = g == 0 ? lo : __builtin_bit_cast(bf16x8, z);
+      }
+    }
   }
 
   f32x16 o[QB][Sh::DB];
@@ -177,6 +188,23 @@ __global__ __launch_bounds__(64 * NW, QB == 1 ? (DHP == 64 ? 4 : DHP <= 96 ? 3 :
   const bool wave_active = w.q0 + wave * QB * 32 < seg_end;
   if (w.seg_len >= AKV) load_tile(0, std::false_type{});
   else load_tile(0, std::true_type{});
+  // What the loader never writes must still be finite (a product with garbage could be NaN): the K rows' columns
+  // DHP .. DHL - 1 take part in S^T and are zero; the V^T rows DHP .. 32 DB - 1 only produce O^T rows that are
+  // never stored, and are zeroed too.  Both stages, once.
+  if constexpr (Sh::DHL > DHP || Sh::DB * 32 > DHP) {
+#pragma unroll
+    for (int stg = 0; stg < 2; ++stg) {
+      unsigned char* sK = lds + stg * Sh::STAGE;
+      unsigned char* sVt = sK + Sh::K_BYTES;
+      if constexpr (Sh::DHL > DHP) {
+        static_assert(Sh::DHL - DHP == 8 || Sh::DHL == DHP, "at most one 16-byte chunk of padding per K row");
+        for (int key = tid; key < AKV; key += ANT) *(u32x4*)(sK + key * Sh::K_STRIDE + DHP * 2) = u32x4{0u, 0u, 0u, 0u};
+      }
+      constexpr int PAD_ROWS = Sh::DB * 32 - DHP, WORDS = AKV / 2;  // 4-byte words per V^T row
+      for (int it = tid; it < PAD_ROWS * WORDS; it += ANT)
+        *(uint32_t*)(sVt + (DHP + it / WORDS) * Sh::VT_STRIDE + (it % WORDS) * 4) = 0u;
+    }
+  }
   store_tile(lds, lds + Sh::K_BYTES);
   __syncthreads();
 
@@ -341,6 +369,7 @@ hipError_t launch_attention_bf16(const AttnArgs& a, hipStream_t s) {
   } while (0)
   switch (a.dh_pad) {
     case 64: VIT_ATTN(64, 1, 4); break;
+    case 72: VIT_ATTN(72, 1, 4); break;
     case 80: VIT_ATTN(80, 1, 4); break;
     case 96: VIT_ATTN(96, 1, 4); break;
     case 128: VIT_ATTN(128, 1, 4); break;

@@ -108,7 +108,9 @@ bool derive(const vit_config_t* c, Dims* d, const char** why) {
   d->g = d->S / d->p; d->P = d->g * d->g; d->T = d->P + c->has_cls;
   d->Kp = d->C * d->p * d->p; d->Kp_pad = (int)round_up(d->Kp, 64);
   d->D = c->hidden; d->H = c->heads; d->dh = dh; d->M = c->mlp;
-  d->dhp = dh <= 64 ? 64 : dh <= 80 ? 80 : dh <= 96 ? 96 : 128;
+  // head dims the attention kernels take as they are; every other one is stored padded to the next of these
+  // (zero weight rows / columns), with the true head dim in the logit scale
+  d->dhp = dh <= 64 ? 64 : dh == 72 ? 72 : dh <= 80 ? 80 : dh <= 96 ? 96 : 128;
   d->Dp = (int)round_up(d->D, 64);
   d->QKVN = 3 * d->H * d->dhp;
   d->Op = (int)round_up(d->H * d->dhp, 64);
