@@ -181,8 +181,8 @@ __device__ __forceinline__ void wave_epilogue_p(const GemmArgs& a, f32x16 (&acc)
                                                 int ncol0, int lane) {
   constexpr int FM = 4, FN = 2;
   const int lrow = lane & 31, lk = lane >> 5;
-  f32x4 bias[FN][4];  // per accumulator quad (the residual path adds its bias after the LDS round trip instead)
-  if constexpr (EPI != EPI_BIAS_RESIDUAL) {
+  f32x4 bias[FN][4];  // per accumulator quad (the fp32 paths add their bias after the LDS round trip instead)
+  if constexpr (EPI == EPI_BIAS || EPI == EPI_BIAS_GELU) {
 #pragma unroll
     for (int j = 0; j < FN; ++j)
 #pragma unroll
@@ -190,26 +190,57 @@ __device__ __forceinline__ void wave_epilogue_p(const GemmArgs& a, f32x16 (&acc)
   }
 
   if constexpr (EPI == EPI_PATCH) {
+    // rows are (tile, patch); the residual stream row is tile * T + cls + patch, and that token's position row is
+    // added.  Staged like the residual epilogue below (16 rows x 32 fp32 columns per piece, read back as 8 lanes
+    // per row), so that the stream is written and the position table read in whole 128-byte row pieces; the row
+    // mapping of a 32-row block is worked out once and serves both of its column blocks.
+    const int sr0 = lane >> 3, sc = (lane & 7) * 4;
+    f32x4 brow[FN];
+#pragma unroll
+    for (int j = 0; j < FN; ++j) brow[j] = *(const f32x4*)(a.bias + ncol0 + j * 32 + sc);
 #pragma unroll
     for (int i = 0; i < FM; ++i) {
-      const int row = row0 + i * 32 + lrow;
-      if (row >= a.M) continue;
-      const int tile = row / a.patches, tok = a.cls + (row - tile * a.patches);
-      float* xr = a.resid + ((size_t)tile * a.tokens + tok) * a.ldo;
-      const float* pr = a.pos + (size_t)tok * a.ldo;
+      size_t dst_off[2][2], pos_off[2][2];  // [half][pass], in elements, of this lane's row
+      bool ok[2][2];
 #pragma unroll
-      for (int j = 0; j < FN; ++j)
+      for (int half = 0; half < 2; ++half)
 #pragma unroll
-        for (int jj = 0; jj < 4; ++jj) {
-          const int col = ncol0 + j * 32 + jj * 8 + lk * 4;
-          if (col < a.N) {
-            const f32x4 p = *(const f32x4*)(pr + col);
-            f32x4 v;
-#pragma unroll
-            for (int e = 0; e < 4; ++e) v[e] = acc[i][j][jj * 4 + e] + bias[j][jj][e] + p[e];
-            *(f32x4*)(xr + col) = v;
-          }
+        for (int p = 0; p < 2; ++p) {
+          const int row = row0 + i * 32 + half * 16 + p * 8 + sr0;
+          ok[half][p] = FULL || row < a.M;
+          const int rr = ok[half][p] ? row : 0;
+          const int tile = rr / a.patches, tok = a.cls + (rr - tile * a.patches);
+          dst_off[half][p] = ((size_t)tile * a.tokens + tok) * a.ldo;
+          pos_off[half][p] = (size_t)tok * a.ldo;
         }
+#pragma unroll
+      for (int j = 0; j < FN; ++j) {
+        const int col = ncol0 + j * 32 + sc;
+        const bool col_ok = FULL || col < a.N;
+        f32x4 posv[2][2];
+#pragma unroll
+        for (int half = 0; half < 2; ++half)
+#pragma unroll
+          for (int p = 0; p < 2; ++p)
+            posv[half][p] = ok[half][p] && col_ok ? *(const f32x4*)(a.pos + pos_off[half][p] + col) : f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int half = 0; half < 2; ++half) {
+          if ((lrow >> 4) == half) {
+#pragma unroll
+            for (int jj = 0; jj < 4; ++jj) {
+              const f32x4 v = {acc[i][j][jj * 4], acc[i][j][jj * 4 + 1], acc[i][j][jj * 4 + 2], acc[i][j][jj * 4 + 3]};
+              *(f32x4*)(st + (lrow & 15) * D_STAGING_ROW + (jj * 8 + lk * 4) * 4) = v;
+            }
+          }
+          __builtin_amdgcn_wave_barrier();
+#pragma unroll
+          for (int p = 0; p < 2; ++p) {
+            const f32x4 t = *(const f32x4*)(st + (p * 8 + sr0) * D_STAGING_ROW + sc * 4);
+            if (ok[half][p] && col_ok) *(f32x4*)(a.resid + dst_off[half][p] + col) = posv[half][p] + (t + brow[j]);
+          }
+          __builtin_amdgcn_wave_barrier();
+        }
+      }
     }
   } else if constexpr (EPI == EPI_BIAS_RESIDUAL) {
     // Pieces of 16 rows x 32 fp32 columns (128 bytes + pad per staged row); a piece is read back

@@ -106,6 +106,55 @@ __global__ __launch_bounds__(256) void patch_gather_kernel(const float* __restri
   Elem<OutT>::store(out + row * ld + col, v);
 }
 
+// The same gather for image sides that are a multiple of 4, one workgroup per strip of patches (one tile, one
+// patch row gy: g patches): the strip's C * p image rows are read once, 16 bytes per lane and coalesced (an image
+// row is contiguous across the strip's patches), scattered into an LDS image of the strip's g output rows, and
+// written out in 16-byte pieces with the padding columns zero.  Every pixel is read once and every output byte
+// written once with full-width accesses; the element-per-thread form above read 3.2 times the pixel bytes.
+template <typename OutT>
+__global__ __launch_bounds__(256) void patch_gather_strip_kernel(const float* __restrict__ px, OutT* __restrict__ out,
+                                                                 int ld, int C, int S, int p, int g, int K, int Kpad) {
+  extern __shared__ __attribute__((aligned(16))) unsigned char strip_raw[];
+  OutT* strip = (OutT*)strip_raw;  // [g][Kpad]
+  const int tid = threadIdx.x;
+  const long tile = blockIdx.x / g;
+  const int gy = blockIdx.x - (int)tile * g;
+  // padding columns K .. Kpad - 1 of every row
+  const int padc = Kpad - K;
+  for (int it = tid; it < g * padc; it += 256) strip[(it / padc) * Kpad + K + it % padc] = (OutT)0;
+  // image rows r = c * p + py, one wave per row at a time, 4 pixels per lane; pixels past the last whole patch
+  // are dropped.  x / p by a float reciprocal (exact for x < 2^20 with the half added).
+  const int quads = S >> 2, used = g * p;
+  const float inv_p = 1.0f / (float)p;
+  const float* base = px + ((tile * C) * S + (long)gy * p) * S;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6), lane = tid & 63;
+  for (int r = wave; r < C * p; r += 4) {
+    const int c = r / p, py = r - c * p;  // wave-uniform
+    const float* row = base + ((long)c * S + py) * S;
+    OutT* drow = strip + r * p;
+    for (int q = lane; q < quads; q += 64) {
+      const f32x4 v = *(const f32x4*)(row + q * 4);
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        const int x = q * 4 + e;
+        if (x < used) {
+          const int gx = (int)(((float)x + 0.5f) * inv_p), pxx = x - gx * p;
+          OutT* dst = drow + gx * Kpad + pxx;
+          if constexpr (sizeof(OutT) == 2) *dst = f32_to_bf16(v[e]);
+          else *dst = v[e];
+        }
+      }
+    }
+  }
+  __syncthreads();
+  const int chunks = Kpad * (int)sizeof(OutT) / 16;  // 16-byte pieces per output row
+  unsigned char* orow = (unsigned char*)(out + (tile * g * g + (long)gy * g) * ld);
+  for (int it = tid; it < g * chunks; it += 256) {
+    const int row = it / chunks, ch = it - row * chunks;
+    *(u32x4*)(orow + (long)row * ld * sizeof(OutT) + ch * 16) = *(const u32x4*)(strip_raw + ((long)row * Kpad * sizeof(OutT)) + ch * 16);
+  }
+}
+
 // x[tile*T, :] = cls + pos[0, :]
 __global__ __launch_bounds__(256) void cls_rows_kernel(float* __restrict__ x, int ldx, const float* __restrict__ cls,
                                                        const float* __restrict__ pos, int n_tiles, int T, int D) {
@@ -191,8 +240,26 @@ hipError_t launch_patch_gather(const float* pixels, void* patches, int ld, int n
                                int Kpad, int out_bf16, hipStream_t s) {
   const long total = (long)n_tiles * g * g * Kpad;
   if (total <= 0) return hipSuccess;
-  const dim3 grid((unsigned)((total + 255) / 256)), block(256);
   const int K = C * p * p;
+  // strip form: whole float4s per image row, 16-byte output pieces, a strip that fits 64 KiB of LDS
+  const size_t es = out_bf16 ? 2 : 4, strip_bytes = (size_t)g * Kpad * es;
+  if (S % 4 == 0 && (Kpad * es) % 16 == 0 && ((size_t)ld * es) % 16 == 0 && strip_bytes <= 64 * 1024 &&
+      (long)n_tiles * g <= 0x7fffffffL) {
+    const dim3 sgrid((unsigned)(n_tiles * g)), sblock(256);
+    if (out_bf16) {
+      static LdsLimitOnce lim;
+      if (hipError_t e = lim.ensure((const void*)patch_gather_strip_kernel<bf16_t>, 64 * 1024); e != hipSuccess) return e;
+      hipLaunchKernelGGL(patch_gather_strip_kernel<bf16_t>, sgrid, sblock, strip_bytes, s, pixels, (bf16_t*)patches, ld, C, S,
+                         p, g, K, Kpad);
+    } else {
+      static LdsLimitOnce lim;
+      if (hipError_t e = lim.ensure((const void*)patch_gather_strip_kernel<float>, 64 * 1024); e != hipSuccess) return e;
+      hipLaunchKernelGGL(patch_gather_strip_kernel<float>, sgrid, sblock, strip_bytes, s, pixels, (float*)patches, ld, C, S, p,
+                         g, K, Kpad);
+    }
+    return hipGetLastError();
+  }
+  const dim3 grid((unsigned)((total + 255) / 256)), block(256);
   if (out_bf16)
     hipLaunchKernelGGL(patch_gather_kernel<bf16_t>, grid, block, 0, s, pixels, (bf16_t*)patches, ld, total, C, S, p, g,
                        K, Kpad);
