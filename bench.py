@@ -23,10 +23,28 @@ import numpy as np  # noqa: E402
 
 PEAK_BF16_TFLOPS = 2500.0  # MI355X dense bf16 MFMA peak
 HBM_PEAK_GBS = 8000.0
-# HBM-side bytes of all matrix-product launches of ONE cfg3 step, from the two rocprofv3 --pmc runs
-# (FETCH_SIZE x 2.0 + WRITE_SIZE x 1.0, factors from the copy calibration) summarised in
-# profiles/kernels_cfg3_ragged_hbm_traffic.md.  A profile figure, not measured by this script.
-GEMM_TRAFFIC_BYTES_PER_STEP = {"cfg3": 257.4e9}
+# HBM-side bytes of all matrix-product launches of one step come from the committed rocprofv3 --pmc summary of the
+# workload (FETCH_SIZE and WRITE_SIZE runs, scaled by the copy calibration described there): a profile figure, not
+# measured by this script.  The summary names the commit it was taken at; both travel into the JSON line.
+TRAFFIC_PROFILES = {"cfg3": "profiles/kernels_cfg3_ragged_hbm_traffic.md"}
+
+
+def gemm_traffic(workload):
+    """(bytes per step, source) parsed from the profile summary of `workload`, or (None, reason)."""
+    import re
+
+    rel = TRAFFIC_PROFILES.get(workload)
+    if rel is None:
+        return None, "no HBM-traffic profile is committed for this workload"
+    try:
+        text = open(os.path.join(ROOT, rel)).read()
+    except OSError:
+        return None, f"{rel} is missing"
+    m = re.search(r"All matrix-product launches of one step: ([0-9.]+) GB read \+ ([0-9.]+) GB written", text)
+    c = re.search(r"Taken at commit ([0-9a-f]{7,40})", text)
+    if not m:
+        return None, f"{rel} has no matrix-product total"
+    return (float(m.group(1)) + float(m.group(2))) * 1e9, f"{rel} (rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE; taken at commit {c.group(1) if c else 'unknown'})"
 
 
 def flops(cfg, tile_offsets):
@@ -215,6 +233,60 @@ def vendor_gemm(torch, gen):
         del a, w, c
 
 
+def power_trace(args, torch, gen, V):
+    """Socket power and per-XCD shader clocks (amd-smi, twice a second) while the workload's encode step runs back to
+    back for about six seconds.  Context for every fraction of peak this script prints: the device holds its power
+    cap during the step, so its clock, not its issue rate, is what the matrix products run into."""
+    import subprocess
+    import threading
+
+    cfg, ipr, to = gen.make_workload(args.workload)
+    n_images, n_tiles = int(ipr.sum()), int(to[-1])
+    enc = V.VitEncoder(cfg, gen.make_weights(cfg, seed=0), device=0)
+    px = torch.from_numpy(gen.make_pixels(cfg, n_tiles, seed=1)).cuda()
+    n_tok, out_dim, _, _ = enc.query(n_tiles, n_images)
+    out = torch.empty((n_tok, out_dim), dtype=torch.bfloat16 if cfg["dtype"] == "bf16" else torch.float32, device="cuda")
+    samples, stop = [], threading.Event()
+
+    def poll():
+        while not stop.is_set():
+            try:
+                doc = json.loads(subprocess.run(["amd-smi", "metric", "-g", "0", "--power", "--clock", "--json"],
+                                                capture_output=True, text=True, timeout=5).stdout)
+                g = doc["gpu_data"][0] if isinstance(doc, dict) else doc[0]
+                clocks = [g["clock"][k]["clk"]["value"] for k in sorted(g["clock"]) if k.startswith("gfx_")]
+                samples.append({"t": time.perf_counter(), "socket_power_w": g["power"]["socket_power"]["value"],
+                                "gfx_clock_mhz": clocks})
+            except Exception as e:  # the tool is missing or its output changed: report, do not fail the run
+                samples.append({"t": time.perf_counter(), "error": repr(e)[:200]})
+            stop.wait(0.5)
+
+    for _ in range(2):
+        enc.encode(px, ipr, to, out=out)
+    torch.cuda.synchronize()
+    th = threading.Thread(target=poll, daemon=True)
+    t0 = time.perf_counter()
+    th.start()
+    steps = 0
+    while time.perf_counter() - t0 < 6.0:
+        enc.encode(px, ipr, to, out=out)
+        torch.cuda.synchronize()
+        steps += 1
+    t1 = time.perf_counter()
+    stop.set()
+    th.join(timeout=10)
+    enc.close()
+    busy = [s for s in samples if "error" not in s and t0 + 1.0 <= s["t"] <= t1]  # skip the ramp of the first second
+    result = {"power_trace": args.workload, "steps": steps, "ms_per_step": (t1 - t0) / steps * 1e3,
+              "samples": len(busy), "errors": [s["error"] for s in samples if "error" in s][:2]}
+    if busy:
+        pw = [float(s["socket_power_w"]) for s in busy]
+        ck = [float(c) for s in busy for c in s["gfx_clock_mhz"]]
+        result.update({"socket_power_w": {"mean": sum(pw) / len(pw), "min": min(pw), "max": max(pw)},
+                       "gfx_clock_mhz": {"mean": sum(ck) / len(ck), "min": min(ck), "max": max(ck)}})
+    print(json.dumps(result))
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -231,6 +303,9 @@ def main():
                          "and print measured encode latencies beside the event model's")
     ap.add_argument("--vendor-gemm", action="store_true",
                     help="time the vendor library's bf16 matrix product (torch.matmul) on the step's shapes: context only")
+    ap.add_argument("--power-trace", action="store_true",
+                    help="run the workload's step back to back for six seconds while sampling socket power and shader "
+                         "clocks with amd-smi; prints one JSON line (context for the fractions of peak)")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="run five plain 1 GiB device copies and exit (scale reference for rocprofv3 FETCH_SIZE / WRITE_SIZE)")
     args = ap.parse_args()
@@ -256,6 +331,9 @@ def main():
         return
     if args.vendor_gemm:
         vendor_gemm(torch, gen)
+        return
+    if args.power_trace:
+        power_trace(args, torch, gen, V)
         return
     if args.sweep:
         sweep(args, torch, gen, V)
@@ -323,13 +401,14 @@ def main():
         fam_ms = {k: v[0] / args.steps for k, v in prof.items()}
         gemm_ms, gemm_n = prof["gemm"][0] / args.steps, prof["gemm"][1] // args.steps
         achieved = gemm_f / (gemm_ms * 1e-3) / 1e12
+        traffic, traffic_source = gemm_traffic(args.workload)
         result["roofline"] = {
             "bound": "mfma", "kernel": "gemm_bf16_dma_kernel (all matrix products of one step; those of fewer than 384 tiles of 256x256 run as gemm_bf16_ring_kernel)",
             "achieved": achieved, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": achieved / PEAK_BF16_TFLOPS,
             # register-only MFMA loop on this device, TFLOP/s: operands random like real data / one constant
             "measured_mfma_ceiling": V.vit_mfma_ceiling(0, 0.1, True),
             "measured_mfma_ceiling_constant_operands": V.vit_mfma_ceiling(0, 0.1, False),
-            "traffic": GEMM_TRAFFIC_BYTES_PER_STEP.get(args.workload), "traffic_unit": "bytes per step (all launches), rocprofv3 --pmc",
+            "traffic": traffic, "traffic_unit": "bytes per step (all launches)", "traffic_source": traffic_source,
             "launches_per_step": int(gemm_n), "ms_per_step": gemm_ms,
             "avg_launch_ms": gemm_ms / max(gemm_n, 1), "flop_per_step": gemm_f,
         }

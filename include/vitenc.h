@@ -80,7 +80,9 @@ typedef struct {
 size_t vit_weight_count(const vit_config_t* cfg);
 
 /*
- * Build an encoder on HIP device `device`.
+ * Build an encoder on HIP device `device`: one Image Instance's model (paper Sec. 4, "Image
+ * Instances": the image encoder is deployed and scaled on its own, apart from the language model;
+ * Sec. 2 "Image Encoding": a vision transformer that turns preprocessed tiles into image tokens).
  *   weights   HOST pointer, n_weights fp32 values in the order above.  The library
  *             converts (round-to-nearest-even to bf16 when dtype is bf16), pads and uploads
  *             them; the caller keeps ownership and may free the buffer on return.
@@ -93,7 +95,10 @@ vit_status_t vit_encoder_create(const vit_config_t* cfg, const float* weights, s
 
 /*
  * Pure host function: what a launch over n_tiles tiles grouped into n_images images
- * produces and needs.  n_tokens = n_tiles * T_out; out_dim = last projector width, or D
+ * produces and needs.  The token count is a function of the tile count alone (paper Sec. 2 and
+ * Table 1: tiles of a fixed size yield a fixed number of tokens each, e.g. 4 x 1601 or
+ * 10 x 729 or 5 x 256 per image), which is what lets a router account for image-token load
+ * before any pixel is encoded (Sec. 4.3).  n_tokens = n_tiles * T_out; out_dim = last projector width, or D
  * (token_merge^2 * D with token down-sampling and no projector);
  * workspace_bytes is an upper bound valid for any grouping of n_tiles tiles into
  * n_images >= 1 images.  Any output pointer may be NULL.
@@ -154,7 +159,8 @@ vit_status_t vit_encode_packed_static(vit_encoder_t* enc, const float* pixels,
                                       size_t out_capacity_bytes, int64_t* request_token_offsets,
                                       void* stream);
 
-/* Free device weights and the handle.  NULL is allowed.  The caller must have drained
+/* Free device weights and the handle (an Image Instance scaled in by the pool manager, paper
+ * Sec. 4.2, releases its encoder this way).  NULL is allowed.  The caller must have drained
  * every stream the handle was used on. */
 void vit_encoder_destroy(vit_encoder_t* enc);
 

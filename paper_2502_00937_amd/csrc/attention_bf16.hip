@@ -12,15 +12,16 @@
 // place: registers 8s..8s+7 of an S^T block are exactly the 8 k-values lane group g feeds
 // to k-step s, provided V^T is read in the same key order (keys 16s + 8jj + 4g + i).
 //
-// On gfx950 the VALU instructions of a SIMD hardly overlap its MFMAs, so the softmax arithmetic
-// (exp2, fma, max, sum, convert) and the two products share one issue budget, and the kernel is
-// shaped around instruction count and latency hiding: a wave owns 32 queries, which keeps it at
-// 124-168 VGPRs so that three or four waves (from different workgroups) share a SIMD and the
-// hardware interleaves their dependency chains; the logit scale is folded into the exp2 argument
-// (one fma per element); full key tiles carry no mask code at all (a segment's last tile is a
-// separate instantiation that also skips an empty key half, and waves with no valid query row skip
-// the arithmetic); the row maximum is not computed on the common path: the reference maximum moves, and
-// the output accumulator is rescaled, only when a row sum of exponentials reaches 2^64.
+// The vector instructions of one wave do overlap the MFMAs of another wave on the same SIMD (a probe: a wave
+// issuing only MFMAs keeps its 32 clocks per instruction while a second wave on the SIMD issues fma or exp2
+// back to back and is slowed by about 12 %), so the kernel is shaped around the number of waves per SIMD and the
+// vector instruction count per 32 x 32 block of logits: a wave owns 32 queries, which keeps it at 128-168 VGPRs
+// so that four (head dim 64) or three waves from different workgroups share a SIMD and interleave their
+// dependency chains (a fourth wave is worth 7 % at head dim 64); the queries arrive multiplied by
+// log2(e) / sqrt(head dim), so the logits are exp2 arguments as they leave the first product; full key tiles
+// carry no mask code at all (a segment's last tile is a separate instantiation that also skips an empty key
+// half, and waves with no valid query row skip the arithmetic); and the normal pass uses no reference maximum:
+// see `attend` below.
 // K/V tiles of 64 keys are double-buffered in LDS: the next tile's global loads are issued before
 // the current tile is processed and written to the other buffer afterwards (one barrier per tile).
 #include <type_traits>
@@ -32,6 +33,7 @@ namespace vitenc {
 namespace {
 
 constexpr int AKV = 64;  // keys per LDS tile
+enum { SUM_VALU = 0, SUM_ROWS = 1 };
 constexpr float REFERENCE_LIMIT = 18446744073709551616.0f;  // 2^64: a row sum this large moves the reference maximum
 
 // QB = 32-query blocks per wave, NW = waves per workgroup: a work item is 32 * QB * NW query rows.
@@ -56,10 +58,15 @@ struct AttnShape {
   static constexpr int K_ITEMS = AKV * NCH;        // 16-byte chunks of the K tile
   static constexpr int V_ITEMS = (AKV / 2) * NCH;  // (key pair, chunk) items of the V tile
   static constexpr int K_PER = (K_ITEMS + ANT - 1) / ANT, V_PER = (V_ITEMS + ANT - 1) / ANT;
+  // where the row sums of P come from in the fast pass: spare rows of the last O^T block if the head dim leaves
+  // any (72, 80), additions otherwise.  (One more accumulator fed by a fragment of ones held in registers costs
+  // 20 registers: at head dim 64 that is the fourth wave of a SIMD, and the kernel came out 5 % slower with it
+  // than with the additions, 13 % when forced into 128 registers.)
+  static constexpr int SUM = DB * 32 - DHP >= 8 ? SUM_ROWS : SUM_VALU;
 };
 
 template <int DHP, int QB, int NW>
-__global__ __launch_bounds__(64 * NW, QB == 1 ? (DHP == 64 ? 4 : DHP <= 96 ? 3 : 2) : 2) void attention_bf16_kernel(const AttnArgs a, float scale_log2) {
+__global__ __launch_bounds__(64 * NW, QB == 1 ? (DHP == 64 ? 4 : DHP <= 96 ? 3 : 2) : 2) void attention_bf16_kernel(const AttnArgs a) {
   using Sh = AttnShape<DHP, QB, NW>;
   constexpr int ANT = Sh::ANT;
   extern __shared__ __attribute__((aligned(16))) unsigned char lds[];  // 2 stages of (K tile, V^T tile)
@@ -96,17 +103,6 @@ __global__ __launch_bounds__(64 * NW, QB == 1 ? (DHP == 64 ? 4 : DHP <= 96 ? 3 :
       }
     }
   }
-
-  f32x16 o[QB][Sh::DB];
-#pragma unroll
-  for (int qb = 0; qb < QB; ++qb)
-#pragma unroll
-    for (int b = 0; b < Sh::DB; ++b)
-#pragma unroll
-      for (int v = 0; v < 16; ++v) o[qb][b][v] = 0.f;
-  float m[QB], l[QB];  // running max (in log2 units) and sum per query
-#pragma unroll
-  for (int qb = 0; qb < QB; ++qb) { m[qb] = -INFINITY; l[qb] = 0.f; }
 
   u32x4 rk[Sh::K_PER], rv0[Sh::V_PER], rv1[Sh::V_PER];
   // global -> registers.  Each thread's (row, column) inside a tile is fixed, so its byte offsets
@@ -186,11 +182,12 @@ __global__ __launch_bounds__(64 * NW, QB == 1 ? (DHP == 64 ? 4 : DHP <= 96 ? 3 :
   const int n_tiles = (w.seg_len + AKV - 1) / AKV;
   // a wave whose 32 * QB query rows all lie past the segment end (last block of a segment) skips the arithmetic
   const bool wave_active = w.q0 + wave * QB * 32 < seg_end;
-  if (w.seg_len >= AKV) load_tile(0, std::false_type{});
-  else load_tile(0, std::true_type{});
+
   // What the loader never writes must still be finite (a product with garbage could be NaN): the K rows' columns
-  // DHP .. DHL - 1 take part in S^T and are zero; the V^T rows DHP .. 32 DB - 1 only produce O^T rows that are
-  // never stored, and are zeroed too.  Both stages, once.
+  // DHP .. DHL - 1 take part in S^T and are zero.  The V^T rows DHP .. 32 DB - 1 only produce O^T rows that are
+  // never stored; they are zero, except that with SUM_ROWS two of them hold ones, so that the row sums of P come
+  // out of the second product for nothing (row DHP for the lanes with g = 0, row DHP + 4 for those with g = 1:
+  // the same accumulator register).  Both stages, once.
   if constexpr (Sh::DHL > DHP || Sh::DB * 32 > DHP) {
 #pragma unroll
     for (int stg = 0; stg < 2; ++stg) {
@@ -201,139 +198,187 @@ __global__ __launch_bounds__(64 * NW, QB == 1 ? (DHP == 64 ? 4 : DHP <= 96 ? 3 :
         for (int key = tid; key < AKV; key += ANT) *(u32x4*)(sK + key * Sh::K_STRIDE + DHP * 2) = u32x4{0u, 0u, 0u, 0u};
       }
       constexpr int PAD_ROWS = Sh::DB * 32 - DHP, WORDS = AKV / 2;  // 4-byte words per V^T row
-      for (int it = tid; it < PAD_ROWS * WORDS; it += ANT)
-        *(uint32_t*)(sVt + (DHP + it / WORDS) * Sh::VT_STRIDE + (it % WORDS) * 4) = 0u;
+      for (int it = tid; it < PAD_ROWS * WORDS; it += ANT) {
+        const int r = it / WORDS;
+        const uint32_t fill = Sh::SUM == SUM_ROWS && (r == 0 || r == 4) ? 0x3F803F80u : 0u;  // two bf16 ones
+        *(uint32_t*)(sVt + (DHP + r) * Sh::VT_STRIDE + (it % WORDS) * 4) = fill;
+      }
     }
   }
-  store_tile(lds, lds + Sh::K_BYTES);
-  __syncthreads();
 
-  // One K/V tile.  MASK is set only for a segment's last, partial tile: full tiles carry no
-  // per-logit compare/select at all.
-  auto process_tile = [&](int t, auto mask_tag) {
-    constexpr bool MASK = decltype(mask_tag)::value;
-    const unsigned char* sK = lds + (t & 1) * Sh::STAGE;
-    const unsigned char* sVt = sK + Sh::K_BYTES;
-    if (t + 1 < n_tiles) {  // the next tile is full unless it is the segment's last, partial one
-      if ((t + 2) * AKV <= w.seg_len) load_tile((t + 1) * AKV, std::false_type{});
-      else load_tile((t + 1) * AKV, std::true_type{});
-    }
+  f32x16 o[QB][Sh::DB];
+  float l[QB];  // row sums of P (FAST with SUM_VALU, and the general pass)
+  float m[QB];  // reference maximum in log2 units (general pass)
 
-    const int remaining = w.seg_len - t * AKV;  // valid keys in this tile (may exceed AKV)
-    // the tile is processed in two 32-key halves to keep S^T and P^T small in registers
+  // One pass over the segment's K/V tiles.
+  //
+  // FAST (the pass that normally is the only one): P^T = exp2(S^T) with no reference maximum at all.  The logits
+  // arrive in log2 units (the QKV product has multiplied the queries by log2(e) / sqrt(head dim)), P is a bf16
+  // value and the sums are fp32, eight exponent bits both, so nothing is lost while the row sum stays between
+  // 2^-100 and 2^100, i.e. while the largest logit of a row lies within about +-69 (natural units) of zero.  That
+  // is checked once, after the last tile; a workgroup with a row outside runs the general pass instead.  Per
+  // 32 x 32 block of logits this pass issues 16 exp2, 8 packed conversions and its MFMAs; the row sums come from
+  // the matrix cores where the head dim leaves spare rows in the last O^T block (SUM_ROWS: two rows of ones in the
+  // V^T tile's padding), else from 16 additions (SUM_VALU).
+  //
+  // General pass: the online softmax with a lazily moving reference maximum m.  m only has to keep exp2 in range,
+  // not to be the exact running maximum, so the row maximum is not computed on its common path either: a row sum
+  // that reaches 2^64 (or is not a number: m = -inf before the first tile) says that m has to move; only then is
+  // the maximum of the half tile taken, m moved and the accumulators rescaled.
+  auto attend = [&](auto fast_tag) {
+    constexpr bool FAST = decltype(fast_tag)::value;
+    constexpr int SUM = FAST ? Sh::SUM : SUM_VALU;
 #pragma unroll
-    for (int kb = 0; kb < 2; ++kb) {
-      if (!wave_active) break;  // (the wave still stages K / V and meets the barriers)
-      if (MASK && kb * 32 >= remaining) break;  // the second half of the last tile may hold no key at all
-      // ---- S^T = K . Q^T: each K fragment feeds all query blocks of the wave; keys past the segment end are
-      //      masked (only a segment's last tile has any)
-      f32x16 st[QB];
-      auto mask = [&](f32x16& sq) {
-        if (MASK) {
-#pragma unroll
-          for (int v = 0; v < 16; ++v) {
-            const int key = kb * 32 + 8 * (v >> 2) + 4 * g + (v & 3);
-            if (key >= remaining) sq[v] = -INFINITY;
-          }
-        }
-      };
-#pragma unroll
-      for (int qb = 0; qb < QB; ++qb)
-#pragma unroll
-        for (int v = 0; v < 16; ++v) st[qb][v] = 0.f;
-#pragma unroll
-      for (int ks = 0; ks < Sh::KS; ++ks) {
-        const bf16x8 kf = *(const bf16x8*)(sK + (kb * 32 + lq) * Sh::K_STRIDE + (ks * 2 + g) * 16);
-#pragma unroll
-        for (int qb = 0; qb < QB; ++qb)
-          st[qb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[qb][ks], st[qb], 0, 0, 0);
-      }
-#pragma unroll
-      for (int qb = 0; qb < QB; ++qb) mask(st[qb]);
-      // ---- online softmax per query block; P^T replaces S^T as bf16 fragments
-      bf16x8 pf[QB][2];
-#pragma unroll
-      for (int qb = 0; qb < QB; ++qb) {
-        // P^T = exp2(S^T * scale - m) with the reference maximum m as it stands.  m only has to keep exp2
-        // in range, not to be the exact running maximum: P is a bf16 value and the sums are fp32, both with
-        // eight exponent bits, so logits may exceed m by 2^6 log2 units before anything is lost.  The row
-        // maximum is therefore not computed at all on the common path; a row sum that reaches 2^64 (or is
-        // not a number: m = -inf before the first tile) says that m has to move.
-        float psum;
-        auto exponentials = [&](const f32x16& sq, float neg_m) {
-          psum = 0.f;
-#pragma unroll
-          for (int s2 = 0; s2 < 2; ++s2) {
-            float p[8];
-#pragma unroll
-            for (int e = 0; e < 8; ++e) {
-              p[e] = __builtin_amdgcn_exp2f(fmaf(sq[s2 * 8 + e], scale_log2, neg_m));
-              psum += p[e];
-            }
-            const u32x4 pk = {pack_bf16x2(p[0], p[1]), pack_bf16x2(p[2], p[3]), pack_bf16x2(p[4], p[5]),
-                              pack_bf16x2(p[6], p[7])};
-            pf[qb][s2] = __builtin_bit_cast(bf16x8, pk);
-          }
-        };
-        exponentials(st[qb], -m[qb]);
-        if (__builtin_amdgcn_ballot_w64(!(psum < REFERENCE_LIMIT)) != 0) {
-          // Rare: move m to the maximum seen so far (the same for the two lanes that share a query), rescale
-          // the accumulators and redo the exponentials.  (Forming the logits again here instead of keeping
-          // them alive costs head dims 80 and 96 seven per cent: measured.)
-          const f32x16& sr = st[qb];
-          float mx = sr[0];
-#pragma unroll
-          for (int v = 1; v < 16; ++v) mx = fmaxf(mx, sr[v]);
-          mx = fmaxf(mx, __builtin_bit_cast(float, __builtin_amdgcn_ds_bpermute(partner_addr, __builtin_bit_cast(int, mx))));
-          const float m_up = fmaxf(m[qb], mx * scale_log2);
-          const float corr = __builtin_amdgcn_exp2f(m[qb] - m_up);
-          l[qb] *= corr;
-#pragma unroll
-          for (int b = 0; b < Sh::DB; ++b)
-#pragma unroll
-            for (int v = 0; v < 16; ++v) o[qb][b][v] *= corr;
-          m[qb] = m_up;
-          exponentials(sr, -m[qb]);
-        }
-        l[qb] += psum;
-      }
-      // ---- O^T += V^T . P^T: each V^T fragment feeds all query blocks of the wave
+    for (int qb = 0; qb < QB; ++qb) {
 #pragma unroll
       for (int b = 0; b < Sh::DB; ++b)
 #pragma unroll
-        for (int s2 = 0; s2 < 2; ++s2) {
-          const unsigned char* p = sVt + (b * 32 + lq) * Sh::VT_STRIDE + (kb * 32 + s2 * 16 + 4 * g) * 2;
-          const u32x2 lo = *(const u32x2*)p, hi = *(const u32x2*)(p + 16);
-          const u32x4 packed = {lo[0], lo[1], hi[0], hi[1]};
-          const bf16x8 vf = __builtin_bit_cast(bf16x8, packed);
+        for (int v = 0; v < 16; ++v) o[qb][b][v] = 0.f;
+      m[qb] = -INFINITY;
+      l[qb] = 0.f;
+    }
+    if (w.seg_len >= AKV) load_tile(0, std::false_type{});
+    else load_tile(0, std::true_type{});
+    store_tile(lds, lds + Sh::K_BYTES);
+    __syncthreads();
+
+    // One K/V tile.  MASK is set only for a segment's last, partial tile: full tiles carry no
+    // per-logit compare/select at all.
+    auto process_tile = [&](int t, auto mask_tag) {
+      constexpr bool MASK = decltype(mask_tag)::value;
+      const unsigned char* sK = lds + (t & 1) * Sh::STAGE;
+      const unsigned char* sVt = sK + Sh::K_BYTES;
+      if (t + 1 < n_tiles) {  // the next tile is full unless it is the segment's last, partial one
+        if ((t + 2) * AKV <= w.seg_len) load_tile((t + 1) * AKV, std::false_type{});
+        else load_tile((t + 1) * AKV, std::true_type{});
+      }
+
+      const int remaining = w.seg_len - t * AKV;  // valid keys in this tile (may exceed AKV)
+      // the tile is processed in two 32-key halves to keep S^T and P^T small in registers
+#pragma unroll
+      for (int kb = 0; kb < 2; ++kb) {
+        if (!wave_active) break;  // (the wave still stages K / V and meets the barriers)
+        if (MASK && kb * 32 >= remaining) break;  // the second half of the last tile may hold no key at all
+        // ---- S^T = K . Q^T: each K fragment feeds all query blocks of the wave; keys past the segment end are
+        //      masked (only a segment's last tile has any)
+        f32x16 st[QB];
+#pragma unroll
+        for (int qb = 0; qb < QB; ++qb)
+#pragma unroll
+          for (int v = 0; v < 16; ++v) st[qb][v] = 0.f;
+#pragma unroll
+        for (int ks = 0; ks < Sh::KS; ++ks) {
+          const bf16x8 kf = *(const bf16x8*)(sK + (kb * 32 + lq) * Sh::K_STRIDE + (ks * 2 + g) * 16);
 #pragma unroll
           for (int qb = 0; qb < QB; ++qb)
-            o[qb][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, pf[qb][s2], o[qb][b], 0, 0, 0);
+            st[qb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[qb][ks], st[qb], 0, 0, 0);
         }
-    }
+        if (MASK) {
+#pragma unroll
+          for (int qb = 0; qb < QB; ++qb)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) {
+              const int key = kb * 32 + 8 * (v >> 2) + 4 * g + (v & 3);
+              if (key >= remaining) st[qb][v] = -INFINITY;
+            }
+        }
+        // ---- P^T replaces S^T as bf16 fragments
+        bf16x8 pf[QB][2];
+#pragma unroll
+        for (int qb = 0; qb < QB; ++qb) {
+          float psum;
+          auto exponentials = [&](const f32x16& sq, float neg_m) {
+            psum = 0.f;
+#pragma unroll
+            for (int s2 = 0; s2 < 2; ++s2) {
+              float p[8];
+#pragma unroll
+              for (int e = 0; e < 8; ++e) {
+                p[e] = __builtin_amdgcn_exp2f(FAST ? sq[s2 * 8 + e] : sq[s2 * 8 + e] + neg_m);
+                if (SUM == SUM_VALU) psum += p[e];
+              }
+              const u32x4 pk = {pack_bf16x2(p[0], p[1]), pack_bf16x2(p[2], p[3]), pack_bf16x2(p[4], p[5]),
+                                pack_bf16x2(p[6], p[7])};
+              pf[qb][s2] = __builtin_bit_cast(bf16x8, pk);
+            }
+          };
+          exponentials(st[qb], -m[qb]);
+          if constexpr (!FAST) {
+            if (__builtin_amdgcn_ballot_w64(!(psum < REFERENCE_LIMIT)) != 0) {
+              // Rare: move m to the maximum seen so far (the same for the two lanes that share a query), rescale
+              // the accumulators and redo the exponentials.  (Forming the logits again here instead of keeping
+              // them alive costs head dims 80 and 96 seven per cent: measured.)
+              const f32x16& sr = st[qb];
+              float mx = sr[0];
+#pragma unroll
+              for (int v = 1; v < 16; ++v) mx = fmaxf(mx, sr[v]);
+              mx = fmaxf(mx, __builtin_bit_cast(float, __builtin_amdgcn_ds_bpermute(partner_addr, __builtin_bit_cast(int, mx))));
+              const float m_up = fmaxf(m[qb], mx);
+              const float corr = __builtin_amdgcn_exp2f(m[qb] - m_up);
+              l[qb] *= corr;
+#pragma unroll
+              for (int b = 0; b < Sh::DB; ++b)
+#pragma unroll
+                for (int v = 0; v < 16; ++v) o[qb][b][v] *= corr;
+              m[qb] = m_up;
+              exponentials(sr, -m[qb]);
+            }
+          }
+          if (SUM == SUM_VALU) l[qb] += psum;
+        }
+        // ---- O^T += V^T . P^T: each V^T fragment feeds all query blocks of the wave
+#pragma unroll
+        for (int b = 0; b < Sh::DB; ++b)
+#pragma unroll
+          for (int s2 = 0; s2 < 2; ++s2) {
+            const unsigned char* p = sVt + (b * 32 + lq) * Sh::VT_STRIDE + (kb * 32 + s2 * 16 + 4 * g) * 2;
+            const u32x2 lo = *(const u32x2*)p, hi = *(const u32x2*)(p + 16);
+            const u32x4 packed = {lo[0], lo[1], hi[0], hi[1]};
+            const bf16x8 vf = __builtin_bit_cast(bf16x8, packed);
+#pragma unroll
+            for (int qb = 0; qb < QB; ++qb)
+              o[qb][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, pf[qb][s2], o[qb][b], 0, 0, 0);
+          }
+      }
 
-    if (t + 1 < n_tiles) {
-      unsigned char* nK = lds + ((t + 1) & 1) * Sh::STAGE;
-      store_tile(nK, nK + Sh::K_BYTES);
+      if (t + 1 < n_tiles) {
+        unsigned char* nK = lds + ((t + 1) & 1) * Sh::STAGE;
+        store_tile(nK, nK + Sh::K_BYTES);
+      }
+      __syncthreads();
+    };
+    // Every load issued so far (the Q fragments among them) has landed before the loop starts: the
+    // compiler's wait-count pass otherwise carries "Q may still be in flight" around the loop and makes
+    // each tile's first MFMAs wait for the global loads of the NEXT tile issued just before them.
+    __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0)
+    const int n_full = w.seg_len / AKV;  // tiles with all 64 keys valid
+    for (int t = 0; t < n_full; ++t) process_tile(t, std::false_type{});
+    if (n_full < n_tiles) process_tile(n_full, std::true_type{});
+
+    // the row sum of every query, in both lanes that share it
+#pragma unroll
+    for (int qb = 0; qb < QB; ++qb) {
+      if constexpr (SUM == SUM_VALU) l[qb] += __shfl_xor(l[qb], 32, 64);
+      else l[qb] = o[qb][Sh::DB - 1][((DHP % 32) / 8) * 4];
     }
-    __syncthreads();
   };
-  // Every load issued so far (the Q fragments among them) has landed before the loop starts: the
-  // compiler's wait-count pass otherwise carries "Q may still be in flight" around the loop and makes
-  // each tile's first MFMAs wait for the global loads of the NEXT tile issued just before them.
-  __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0)
-  const int n_full = w.seg_len / AKV;  // tiles with all 64 keys valid
-  for (int t = 0; t < n_full; ++t) process_tile(t, std::false_type{});
-  if (n_full < n_tiles) process_tile(n_full, std::true_type{});
+
+  attend(std::true_type{});
+  {
+    bool ok = true;
+#pragma unroll
+    for (int qb = 0; qb < QB; ++qb) ok = ok && l[qb] >= 0x1p-100f && l[qb] <= 0x1p100f;  // false for NaN
+    // (the barrier also separates the last tile's LDS reads from the general pass's first stores)
+    if (__syncthreads_or(wave_active && !ok)) attend(std::false_type{});
+  }
 
   // ---- normalise and store: lane owns a query; registers 4j..4j+3 of block b are
   //      d = 32b + 8j + 4g .. +3, four consecutive columns -> one 8-byte store
 #pragma unroll
   for (int qb = 0; qb < QB; ++qb) {
     const int qrow = w.q0 + (wave * QB + qb) * 32 + lq;
-    const float lsum = l[qb] + __shfl_xor(l[qb], 32, 64);
     if (qrow < seg_end) {
-      const float inv = 1.0f / lsum;
+      const float inv = 1.0f / l[qb];
       bf16_t* orow = (bf16_t*)a.out + (size_t)qrow * a.ld_o + head * DHP;
 #pragma unroll
       for (int b = 0; b < Sh::DB; ++b)
@@ -357,7 +402,6 @@ int attention_q_block(int dtype_bf16, int dh_pad) { return !dtype_bf16 ? 64 : 12
 hipError_t launch_attention_bf16(const AttnArgs& a, hipStream_t s) {
   if (a.n_work <= 0) return hipSuccess;
   if (a.ld_qkv % 8 != 0 || a.ld_o % 4 != 0) return hipErrorInvalidValue;
-  const float scale_log2 = 1.4426950408889634f / sqrtf((float)a.dh);
   const dim3 grid(((a.n_work + 7) / 8) * 8, a.heads);
 #define VIT_ATTN(DHP, QB, NW)                                                                            \
   do {                                                                                                 \
@@ -365,7 +409,7 @@ hipError_t launch_attention_bf16(const AttnArgs& a, hipStream_t s) {
     auto kfn = attention_bf16_kernel<DHP, QB, NW>;                                                     \
     static LdsLimitOnce lds_limit; /* raised once per kernel and device */                             \
     if (hipError_t e = lds_limit.ensure((const void*)kfn, smem); e != hipSuccess) return e;            \
-    hipLaunchKernelGGL(kfn, grid, dim3(AttnShape<DHP, QB, NW>::ANT), smem, s, a, scale_log2);          \
+    hipLaunchKernelGGL(kfn, grid, dim3(AttnShape<DHP, QB, NW>::ANT), smem, s, a);                      \
   } while (0)
   switch (a.dh_pad) {
     case 64: VIT_ATTN(64, 1, 4); break;

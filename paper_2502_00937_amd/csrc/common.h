@@ -122,6 +122,8 @@ struct GemmArgs {
   int reverse;        // 1: walk the row blocks from the last to the first (see vit_encode_packed)
   unsigned long long* tile_stamps;  // measurement aid, normally null: [256 workgroups][kTileStampSlots][4] words written
                                     // by the persistent kernel per tile (see vit_profile_tiles_read)
+  int q_cols;         // EPI_BIAS: output columns [0, q_cols) are multiplied by q_scale after the bias (0: none);
+  float q_scale;      //   the QKV product hands the attention kernel its queries times log2(e) / sqrt(head dim)
   int stream_out;     // 1: the bf16 output exceeds the memory-side cache; the persistent kernel stores it non-temporally
 };
 

@@ -98,7 +98,7 @@ __global__ __launch_bounds__(256) void attention_f32_kernel(const AttnArgs a) {
       s += __shfl_xor(s, 1, 64);
       s += __shfl_xor(s, 2, 64);
       const float mn = fmaxf(m, s);
-      const float corr = __expf(m - mn), p = __expf(s - mn);
+      const float corr = expf(m - mn), p = expf(s - mn);  // the library's exp: this mode is for exact-arithmetic parity
       l = l * corr + p;
       m = mn;
 #pragma unroll

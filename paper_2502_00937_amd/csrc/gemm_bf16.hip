@@ -99,6 +99,14 @@ __device__ __forceinline__ void wave_epilogue(const GemmArgs& a, f32x16 (&acc)[F
       __builtin_amdgcn_wave_barrier();
     }
   } else {  // EPI_BIAS, EPI_BIAS_GELU: bf16 output
+    float cs[FN][4];  // column scale of each accumulator quad (see GemmArgs::q_cols); the bias is scaled with it
+#pragma unroll
+    for (int j = 0; j < FN; ++j)
+#pragma unroll
+      for (int jj = 0; jj < 4; ++jj) {
+        cs[j][jj] = EPI == EPI_BIAS && ncol0 + j * 32 + jj * 8 + lk * 4 < a.q_cols ? a.q_scale : 1.0f;
+        bias[j][jj] *= cs[j][jj];
+      }
     unsigned char* st = smem + wave * 32 * STAGE_BF16;
     constexpr int LPR = TN / 8;  // lanes per staged row (16 bytes = 8 bf16 each)
     constexpr int RPI = 64 / LPR;
@@ -111,7 +119,7 @@ __device__ __forceinline__ void wave_epilogue(const GemmArgs& a, f32x16 (&acc)[F
           float v[4];
 #pragma unroll
           for (int e = 0; e < 4; ++e) {
-            v[e] = acc[i][j][jj * 4 + e] + bias[j][jj][e];
+            v[e] = fmaf(acc[i][j][jj * 4 + e], cs[j][jj], bias[j][jj][e]);
             if constexpr (EPI == EPI_BIAS_GELU) v[e] = gelu_fast(v[e]);
           }
           const u32x2 pk = {pack_bf16x2(v[0], v[1]), pack_bf16x2(v[2], v[3])};
@@ -299,6 +307,14 @@ __device__ __forceinline__ void wave_epilogue_p(const GemmArgs& a, f32x16 (&acc)
   } else {  // EPI_BIAS, EPI_BIAS_GELU: bf16 output, pieces of 16 rows x 64 columns (128 bytes + pad)
     // (storing the 8-byte register quads directly was measured slower than this LDS round trip)
     // Store addresses: wave-uniform base (scalar arithmetic) + a per-lane byte offset that never changes.
+    float cs[FN][4];  // column scale of each accumulator quad (see GemmArgs::q_cols); the bias is scaled with it
+#pragma unroll
+    for (int j = 0; j < FN; ++j)
+#pragma unroll
+      for (int jj = 0; jj < 4; ++jj) {
+        cs[j][jj] = EPI == EPI_BIAS && ncol0 + j * 32 + jj * 8 + lk * 4 < a.q_cols ? a.q_scale : 1.0f;
+        bias[j][jj] *= cs[j][jj];
+      }
     const int sc = (lane & 7) * 8;
     const uint32_t lane_off = (uint32_t)((lane >> 3) * a.ldo + sc) * 2u;
     unsigned char* const tile_base = (unsigned char*)a.out + ((size_t)row0 * a.ldo + ncol0) * 2;
@@ -314,7 +330,7 @@ __device__ __forceinline__ void wave_epilogue_p(const GemmArgs& a, f32x16 (&acc)
           float v[4];
 #pragma unroll
           for (int e = 0; e < 4; ++e) {
-            v[e] = acc[i][j][jj * 4 + e] + bias[j][jj][e];
+            v[e] = fmaf(acc[i][j][jj * 4 + e], cs[j][jj], bias[j][jj][e]);
             if constexpr (EPI == EPI_BIAS_GELU) v[e] = gelu_fast(v[e]);
           }
           pk[j][jj] = u32x2{pack_bf16x2(v[0], v[1]), pack_bf16x2(v[2], v[3])};

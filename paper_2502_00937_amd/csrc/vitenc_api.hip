@@ -661,6 +661,11 @@ static vit_status_t encode_impl(const char* fn, vit_encoder_t* e, const float* p
     a.reverse = reverse;
     reverse ^= 1;
     a.stream_out = (size_t)M * lin.N * d.es > kCacheBytes;
+    if (family == VIT_PROF_GEMM_QKV && d.bf16) {
+      // the bf16 attention kernel takes its queries in units of log2: exp2(q . k) is the softmax weight
+      a.q_cols = d.H * d.dhp;
+      a.q_scale = 1.4426950408889634f / sqrtf((float)d.dh);
+    }
     a.tile_stamps = e->tile_stamps && timing ? e->tile_stamps + (size_t)family * kStampWordsPerFamily : nullptr;
     ProfScope ps(e, s, family, timing);
     return d.bf16 ? launch_gemm_bf16(a, s) : launch_gemm_f32(a, s);
