@@ -844,9 +844,33 @@ hipError_t launch_gemm_bf16(const GemmArgs& a, hipStream_t s) {
   // The persistent 256 x 256 kernel pays off from about one and a half tiles per compute unit
   // (measured crossover between 300 and 440 tiles on the encoder's shapes); below that its last,
   // partly filled round costs more than the smaller tiles' extra operand traffic.
-  const long big_tiles = (long)((a.M + 255) / 256) * ((a.N + 255) / 256);
-  if (big_tiles >= 384) return launch_dma(a, s);
-  return launch_ring(a, s);
+  const int tiles_m = (a.M + 255) / 256, tiles_n = (a.N + 255) / 256;
+  const long big_tiles = (long)tiles_m * tiles_n;
+  if (big_tiles < 384) return launch_ring(a, s);
+  // A product one column band wide (1, 2 or 4 tile columns) is walked in rounds of 256 / tiles_n row blocks, one
+  // tile per compute unit.  When the last round holds at most 64 tiles, three quarters or more of the units would
+  // sit out a whole tile time: those row blocks go to the small-tile kernel in a second launch instead (at most
+  // 256 tiles of 128 x 128, one short round).  Both kernels give a row the same bits, so where the cut falls does
+  // not show in the result.  The cut is made at the end the walk reaches last.
+  if (a.epilogue != EPI_PATCH && (tiles_n == 1 || tiles_n == 2 || tiles_n == 4)) {
+    const int per_round = 256 / tiles_n;
+    const int tail_blocks = tiles_m % per_round;
+    if (tail_blocks > 0 && tiles_m > per_round && tail_blocks * tiles_n <= 64) {
+      const int cut = a.reverse ? tail_blocks * 256 : (tiles_m - tail_blocks) * 256;  // first row of the upper part
+      auto rows_from = [&](int row0, int rows) {
+        GemmArgs b = a;
+        b.M = rows;
+        b.A = (const unsigned char*)a.A + (size_t)row0 * a.lda * 2;
+        if (a.out) b.out = (unsigned char*)a.out + (size_t)row0 * a.ldo * 2;
+        if (a.resid) b.resid = a.resid + (size_t)row0 * a.ldo;
+        return b;
+      };
+      const GemmArgs lower = rows_from(0, cut), upper = rows_from(cut, a.M - cut);
+      if (hipError_t e = launch_dma(a.reverse ? upper : lower, s); e != hipSuccess) return e;
+      return launch_ring(a.reverse ? lower : upper, s);
+    }
+  }
+  return launch_dma(a, s);
 }
 
 }  // namespace vitenc
