@@ -133,6 +133,27 @@ def sweep(args, torch, gen, V):
     points = []
     for n in (1, 2, 4, 8, 16, 32, 64, 128, 260):
         points.append((n, timed(n, np.ones(n, dtype=np.int32), "images per launch")))
+    # Host side of a small launch: how long the calling thread is busy issuing it, as ~270 kernel launches and as one
+    # replay of the recorded sequence (vit_encode_packed_graph).  The device time of the launch is the same either way.
+    for n in (1, 8):
+        to = np.arange(n + 1, dtype=np.int32)
+        n_tok, out_dim, _, _ = enc.query(n, n)
+        out = torch.empty((n_tok, out_dim), dtype=torch.bfloat16, device="cuda")
+        pxn = px[:n]
+        host_us = {}
+        for graph in (False, True):
+            for _ in range(3):  # (with graph=True: plain, recording, first replay)
+                enc.encode(pxn, [n], to, out=out, graph=graph)
+            torch.cuda.synchronize()
+            ts = []
+            for _ in range(20):
+                t0 = time.perf_counter()
+                enc.encode(pxn, [n], to, out=out, graph=graph)
+                ts.append(time.perf_counter() - t0)
+                torch.cuda.synchronize()
+            host_us[graph] = float(np.median(ts)) * 1e6
+        print(json.dumps({"host_time_of_one_call": "plain launches against one graph replay", "images": n,
+                          "plain_us": host_us[False], "graph_replay_us": host_us[True]}))
     timed(260, ipr3, "cfg3 as 64 ragged requests")
     timed(260, np.ones(260, dtype=np.int32), "cfg3 as 260 single-image requests")
     timed(260, np.asarray([260], dtype=np.int32), "cfg3 as one request of 260 images")

@@ -159,6 +159,29 @@ vit_status_t vit_encode_packed_static(vit_encoder_t* enc, const float* pixels,
                                       size_t out_capacity_bytes, int64_t* request_token_offsets,
                                       void* stream);
 
+/*
+ * vit_encode_packed for small, launch-bound batches: the paper's image requests mostly carry one
+ * or a few images (Sec. 3.3 "Workload Characteristics": heavy-tailed images per request) and their
+ * encode time sits on the path to the first token (Sec. 3.2), while one 336-px ViT-L image is
+ * some 270 kernel launches that together run shorter than the host needs to issue them.  Same
+ * arguments, results (bit for bit) and errors as vit_encode_packed.  The kernels' arguments are part
+ * of a graph, so a launch sequence is kept per (pixels, out_tokens, workspace, tile_offsets
+ * contents): the first call with a key runs like vit_encode_packed, the second records the sequence
+ * into a HIP graph (on a stream of the library's own, so `stream` may be the default stream), every
+ * later one replays it with one graph launch on `stream`.  The buffers' CONTENTS may change between
+ * calls; a caller that cycles through a fixed pool of buffers hits after the second round.  Eight
+ * sequences are kept per handle, the least recently used is replaced.  Only kernels are recorded:
+ * the attention work lists are written on the device from tile offsets that travel as a kernel
+ * argument, which limits a graphed batch to VIT_STATIC_MAX_IMAGES images; a larger batch runs as
+ * vit_encode_packed does.  Per-kernel timing (vit_profile_*) does not cover these calls.  The first
+ * two calls with a key allocate (key, graph); replays do not.
+ */
+vit_status_t vit_encode_packed_graph(vit_encoder_t* enc, const float* pixels,
+                                     const int32_t* images_per_request, int32_t n_requests,
+                                     const int32_t* tile_offsets, void* out_tokens,
+                                     size_t out_capacity_bytes, int64_t* request_token_offsets,
+                                     void* workspace, size_t workspace_bytes, void* stream);
+
 /* Free device weights and the handle (an Image Instance scaled in by the pool manager, paper
  * Sec. 4.2, releases its encoder this way).  NULL is allowed.  The caller must have drained
  * every stream the handle was used on. */

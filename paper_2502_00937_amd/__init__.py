@@ -11,6 +11,7 @@ from .binding import (  # noqa: F401
     load_library,
     preprocess_tiles,
     vit_encode_packed,
+    vit_encode_packed_graph,
     vit_encode_packed_static,
     vit_encoder_create,
     vit_encoder_destroy,

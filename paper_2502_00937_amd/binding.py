@@ -58,6 +58,8 @@ def load_library():
     lib.vit_encode_packed.restype = C.c_int
     lib.vit_encode_packed.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32, C.c_void_p, C.c_void_p, C.c_size_t,
                                       C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]
+    lib.vit_encode_packed_graph.restype = C.c_int
+    lib.vit_encode_packed_graph.argtypes = lib.vit_encode_packed.argtypes
     lib.vit_encode_packed_static.restype = C.c_int
     lib.vit_encode_packed_static.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32, C.c_void_p, C.c_void_p,
                                              C.c_size_t, C.c_void_p, C.c_void_p]
@@ -146,6 +148,20 @@ def vit_encode_packed(handle: int, pixels_ptr: int, images_per_request, tile_off
     _check(load_library().vit_encode_packed(handle, pixels_ptr, ipr.ctypes.data if ipr.size else None, ipr.size,
                                             to.ctypes.data, out_ptr, out_capacity_bytes, rto.ctypes.data,
                                             workspace_ptr, workspace_bytes, stream))
+    return rto
+
+
+def vit_encode_packed_graph(handle: int, pixels_ptr: int, images_per_request, tile_offsets, out_ptr: int,
+                            out_capacity_bytes: int, workspace_ptr: int, workspace_bytes: int, stream: int = 0):
+    """Raw call of the graph-replaying variant (same arguments as vit_encode_packed)."""
+    ipr = np.ascontiguousarray(images_per_request, dtype=np.int32)
+    to = np.ascontiguousarray(tile_offsets, dtype=np.int32)
+    if (ipr >= 0).all() and to.size != int(ipr.sum()) + 1:
+        raise VitError(VIT_EINVAL, "tile_offsets must have sum(images_per_request) + 1 entries")
+    rto = np.zeros(ipr.size + 1, dtype=np.int64)
+    _check(load_library().vit_encode_packed_graph(handle, pixels_ptr, ipr.ctypes.data if ipr.size else None, ipr.size,
+                                                  to.ctypes.data, out_ptr, out_capacity_bytes, rto.ctypes.data,
+                                                  workspace_ptr, workspace_bytes, stream))
     return rto
 
 
@@ -290,8 +306,10 @@ class VitEncoder:
     def query(self, n_tiles: int, n_images: int):
         return vit_encoder_query(self._handle, n_tiles, n_images)
 
-    def encode(self, pixels, images_per_request, tile_offsets, out=None):
-        """pixels: torch fp32 device tensor [n_tiles, C, S, S].  Returns (tokens, request_token_offsets)."""
+    def encode(self, pixels, images_per_request, tile_offsets, out=None, graph=False):
+        """pixels: torch fp32 device tensor [n_tiles, C, S, S].  Returns (tokens, request_token_offsets).
+        graph=True goes through vit_encode_packed_graph, which replays a recorded launch sequence from the third call
+        with the same `pixels` and `out` tensors and batch shape on (pass `out`: a fresh one per call never repeats)."""
         torch = self._torch
         assert pixels.is_cuda and pixels.dtype == torch.float32 and pixels.is_contiguous()
         check_pixels(self.cfg, pixels.shape, tile_offsets)
@@ -305,8 +323,9 @@ class VitEncoder:
         if self._ws is None or self._ws.numel() < ws_bytes:
             self._ws = torch.empty(max(ws_bytes, 256), dtype=torch.uint8, device=pixels.device)
         stream = torch.cuda.current_stream(pixels.device).cuda_stream
-        rto = vit_encode_packed(self._handle, pixels.data_ptr(), images_per_request, tile_offsets, out.data_ptr(),
-                                out.numel() * out.element_size(), self._ws.data_ptr(), self._ws.numel(), stream)
+        call = vit_encode_packed_graph if graph else vit_encode_packed
+        rto = call(self._handle, pixels.data_ptr(), images_per_request, tile_offsets, out.data_ptr(),
+                   out.numel() * out.element_size(), self._ws.data_ptr(), self._ws.numel(), stream)
         return out, rto
 
     def profile_enable(self, on: bool = True):

@@ -171,6 +171,18 @@ struct StageSlot {
 
 struct ProfRec { int family; hipEvent_t start, stop; };
 
+// One cached launch sequence of vit_encode_packed_graph.  The kernels' pointer arguments are part of a graph, so the
+// key holds the three device buffers beside the batch shape.
+struct GraphEntry {
+  const void* pixels = nullptr;
+  void* out = nullptr;
+  void* workspace = nullptr;
+  std::vector<int32_t> tile_offsets;  // n_images + 1
+  hipGraphExec_t exec = nullptr;      // null until the key has been seen a second time
+  uint64_t used = 0;
+};
+constexpr size_t kMaxGraphs = 8;
+
 constexpr size_t kStampWordsPerFamily = (size_t)256 * kTileStampSlots * 4;
 
 }  // namespace
@@ -194,6 +206,10 @@ struct vit_encoder {
   std::vector<hipEvent_t> free_events;
   double prof_ms[VIT_PROF_COUNT] = {};
   int64_t prof_n[VIT_PROF_COUNT] = {};
+  // vit_encode_packed_graph: launch sequences captured per (buffers, batch shape), least recently used replaced
+  std::vector<GraphEntry> graphs;
+  uint64_t graph_tick = 0;
+  hipStream_t capture_stream = nullptr;
 };
 
 namespace {
@@ -477,6 +493,9 @@ void vit_encoder_destroy(vit_encoder_t* e) {
   if (!e) return;
   (void)hipSetDevice(e->device);
   if (e->tile_stamps) (void)hipHostFree(e->tile_stamps);
+  for (auto& g : e->graphs)
+    if (g.exec) (void)hipGraphExecDestroy(g.exec);
+  if (e->capture_stream) (void)hipStreamDestroy(e->capture_stream);
   for (auto& r : e->prof) { (void)hipEventDestroy(r.start); (void)hipEventDestroy(r.stop); }
   for (auto ev : e->free_events) (void)hipEventDestroy(ev);
   for (auto& s : e->stage) {
@@ -543,13 +562,20 @@ vit_status_t vit_encoder_query(const vit_encoder_t* e, int32_t n_tiles, int32_t 
   return VIT_OK;
 }
 
-// The encode path behind both entry points.  `static_scratch`: the workspace is the calling device's
-// static array, the attention work lists are written by a kernel, and nothing is allocated: no pinned
-// staging, no events (per-kernel timing is off for such a call).
+// The encode path behind the entry points.
+struct EncodeMode {
+  bool static_scratch = false;  // the workspace is the calling device's static array (wording of the capacity error)
+  bool device_tables = false;   // the attention work lists are written by a kernel from the tile offsets (at most
+                                // kStaticMaxImages images); nothing is allocated and nothing but kernels is queued:
+                                // no pinned staging, no copy, no events (per-kernel timing is off for such a call)
+  bool host_only = false;       // validate, fill request_token_offsets, report the image count; launch nothing
+};
 static vit_status_t encode_impl(const char* fn, vit_encoder_t* e, const float* pixels, const int32_t* images_per_request,
                                 int32_t n_requests, const int32_t* tile_offsets, void* out_tokens,
                                 size_t out_capacity_bytes, int64_t* request_token_offsets, void* workspace,
-                                size_t workspace_bytes, void* stream, bool static_scratch) {
+                                size_t workspace_bytes, void* stream, const EncodeMode mode,
+                                int64_t* n_images_out = nullptr) {
+  const bool static_scratch = mode.static_scratch;
   if (!e) return fail(VIT_EINVAL, "%s: NULL encoder", fn);
   if (n_requests < 0) return fail(VIT_EINVAL, "%s: n_requests < 0", fn);
   if (n_requests > 0 && !images_per_request) return fail(VIT_EINVAL, "%s: images_per_request is NULL", fn);
@@ -566,6 +592,7 @@ static vit_status_t encode_impl(const char* fn, vit_encoder_t* e, const float* p
     if (tile_offsets[i + 1] <= tile_offsets[i])
       return fail(VIT_EINVAL, "%s: image %lld has no tiles (tile_offsets must increase)", fn, (long long)i);
   const int64_t n_tiles = tile_offsets[n_images];
+  if (n_images_out) *n_images_out = n_images;
   if (n_tiles * d.T > (int64_t)INT32_MAX - 1024) return fail(VIT_EINVAL, "%s: more than 2^31 token rows", fn);
   if (request_token_offsets) {
     int64_t img = 0;
@@ -589,8 +616,9 @@ static vit_status_t encode_impl(const char* fn, vit_encoder_t* e, const float* p
     return fail(VIT_ECAPACITY, static_scratch ? "%s: the static scratch array holds %zu bytes, this batch needs %zu"
                                               : "%s: workspace holds %zu bytes, %zu needed",
                 fn, workspace_bytes, w.total);
-  if (static_scratch && n_images > kStaticMaxImages)
+  if (mode.device_tables && n_images > kStaticMaxImages)
     return fail(VIT_ECAPACITY, "%s: %lld images, at most %d per call", fn, (long long)n_images, kStaticMaxImages);
+  if (mode.host_only) return VIT_OK;
 
   HIP_TRY(hipSetDevice(e->device));
   hipStream_t s = (hipStream_t)stream;
@@ -606,9 +634,9 @@ static vit_status_t encode_impl(const char* fn, vit_encoder_t* e, const float* p
   // ---- segment planning: blocks of query rows per tile (local layers) and per image (global layers)
   const int bq = attention_q_block(d.bf16, d.dhp);
   const bool has_global = d.L > d.L_loc;
-  const bool timing = !static_scratch;  // events are created on demand: not in a call that may not allocate
+  const bool timing = !mode.device_tables;  // events are created on demand: not in a call that may not allocate
   int n_local = 0, n_global = 0;
-  if (static_scratch) {
+  if (mode.device_tables) {
     // the lists' lengths on the host (launch sizes), their contents by a kernel from the offsets themselves
     n_local = (int)(n_tiles * ((d.T + bq - 1) / bq));
     TileOffsetsArg to;
@@ -744,7 +772,7 @@ vit_status_t vit_encode_packed(vit_encoder_t* e, const float* pixels, const int3
                                size_t out_capacity_bytes, int64_t* request_token_offsets, void* workspace,
                                size_t workspace_bytes, void* stream) {
   return encode_impl("vit_encode_packed", e, pixels, images_per_request, n_requests, tile_offsets, out_tokens,
-                     out_capacity_bytes, request_token_offsets, workspace, workspace_bytes, stream, false);
+                     out_capacity_bytes, request_token_offsets, workspace, workspace_bytes, stream, EncodeMode{});
 }
 
 vit_status_t vit_encode_packed_static(vit_encoder_t* e, const float* pixels, const int32_t* images_per_request,
@@ -754,8 +782,92 @@ vit_status_t vit_encode_packed_static(vit_encoder_t* e, const float* pixels, con
   if (!e->scratch)
     return fail(VIT_EDEVICE, "vit_encode_packed_static: the static scratch array has no address on device %d: %s",
                 e->device, hipGetErrorString(e->scratch_error));
+  EncodeMode mode;
+  mode.static_scratch = mode.device_tables = true;
   return encode_impl("vit_encode_packed_static", e, pixels, images_per_request, n_requests, tile_offsets, out_tokens,
-                     out_capacity_bytes, request_token_offsets, e->scratch, kStaticScratchBytes, stream, true);
+                     out_capacity_bytes, request_token_offsets, e->scratch, kStaticScratchBytes, stream, mode);
+}
+
+vit_status_t vit_encode_packed_graph(vit_encoder_t* e, const float* pixels, const int32_t* images_per_request,
+                                     int32_t n_requests, const int32_t* tile_offsets, void* out_tokens,
+                                     size_t out_capacity_bytes, int64_t* request_token_offsets, void* workspace,
+                                     size_t workspace_bytes, void* stream) {
+  const char* fn = "vit_encode_packed_graph";
+  // every check of the plain call, the host-side result and the image count; nothing launched yet
+  EncodeMode check;
+  check.host_only = true;
+  int64_t n_images = 0;
+  if (vit_status_t st = encode_impl(fn, e, pixels, images_per_request, n_requests, tile_offsets, out_tokens,
+                                    out_capacity_bytes, request_token_offsets, workspace, workspace_bytes, stream, check,
+                                    &n_images);
+      st != VIT_OK)
+    return st;
+  if (tile_offsets[n_images] == 0) return VIT_OK;
+  auto eager = [&](bool device_tables) {
+    EncodeMode m;
+    m.device_tables = device_tables;
+    return encode_impl(fn, e, pixels, images_per_request, n_requests, tile_offsets, out_tokens, out_capacity_bytes,
+                       request_token_offsets, workspace, workspace_bytes, stream, m);
+  };
+  // a graph holds nothing but kernels: batches whose work lists cannot be built on the device run as they are
+  if (n_images > kStaticMaxImages) return eager(false);
+
+  GraphEntry* hit = nullptr;
+  for (auto& g : e->graphs)
+    if (g.pixels == pixels && g.out == out_tokens && g.workspace == workspace &&
+        g.tile_offsets.size() == (size_t)n_images + 1 &&
+        std::equal(g.tile_offsets.begin(), g.tile_offsets.end(), tile_offsets)) {
+      hit = &g;
+      break;
+    }
+  if (!hit) {
+    // first sight of these buffers and this shape: run it as it is (which also leaves every kernel's launch
+    // attributes set) and remember the key; the least recently used entry makes room
+    try {
+      if (e->graphs.size() < kMaxGraphs) {
+        e->graphs.emplace_back();
+        hit = &e->graphs.back();
+      } else {
+        hit = &*std::min_element(e->graphs.begin(), e->graphs.end(),
+                                 [](const GraphEntry& a, const GraphEntry& b) { return a.used < b.used; });
+        if (hit->exec) (void)hipGraphExecDestroy(hit->exec);
+        hit->exec = nullptr;
+      }
+      hit->tile_offsets.assign(tile_offsets, tile_offsets + n_images + 1);
+    } catch (...) {
+      if (hit) hit->tile_offsets.clear(), hit->pixels = nullptr;
+      return eager(true);  // no memory for the key: the call itself does not need it
+    }
+    hit->pixels = pixels; hit->out = out_tokens; hit->workspace = workspace;
+    hit->used = ++e->graph_tick;
+    return eager(true);
+  }
+  hit->used = ++e->graph_tick;
+  HIP_TRY(hipSetDevice(e->device));
+  if (!hit->exec) {
+    // second sight: record the launch sequence on a stream of the library's own (the caller's may be the legacy
+    // default stream, which cannot be captured) and keep the executable graph
+    if (!e->capture_stream) HIP_TRY(hipStreamCreateWithFlags(&e->capture_stream, hipStreamNonBlocking));
+    HIP_TRY(hipStreamBeginCapture(e->capture_stream, hipStreamCaptureModeThreadLocal));
+    EncodeMode m;
+    m.device_tables = true;
+    const vit_status_t st = encode_impl(fn, e, pixels, images_per_request, n_requests, tile_offsets, out_tokens,
+                                        out_capacity_bytes, request_token_offsets, workspace, workspace_bytes,
+                                        e->capture_stream, m);
+    hipGraph_t graph = nullptr;
+    const hipError_t end = hipStreamEndCapture(e->capture_stream, &graph);
+    hipGraphExec_t exec = nullptr;
+    hipError_t inst = hipErrorUnknown;
+    if (st == VIT_OK && end == hipSuccess && graph) inst = hipGraphInstantiate(&exec, graph, nullptr, nullptr, 0);
+    if (graph) (void)hipGraphDestroy(graph);
+    if (inst != hipSuccess) {  // nothing ran during the capture: run the call as it is
+      (void)hipGetLastError();
+      return eager(true);
+    }
+    hit->exec = exec;
+  }
+  HIP_TRY(hipGraphLaunch(hit->exec, (hipStream_t)stream));
+  return VIT_OK;
 }
 
 vit_status_t vit_profile_enable(vit_encoder_t* e, int enable) {

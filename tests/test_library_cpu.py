@@ -142,6 +142,7 @@ def test_create_rejects_null_and_bad_arguments_without_a_device():
     assert st == B.VIT_EINVAL and b"n_weights" in lib.vit_last_error()
     assert lib.vit_encoder_query(None, 1, 1, None, None, None, None) == B.VIT_EINVAL
     assert lib.vit_encode_packed(None, None, None, 0, None, None, 0, None, None, 0, None) == B.VIT_EINVAL
+    assert lib.vit_encode_packed_graph(None, None, None, 0, None, None, 0, None, None, 0, None) == B.VIT_EINVAL
     lib.vit_encoder_destroy(None)  # NULL-safe
 
 
