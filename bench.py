@@ -424,7 +424,7 @@ def main():
         achieved = gemm_f / (gemm_ms * 1e-3) / 1e12
         traffic, traffic_source = gemm_traffic(args.workload)
         result["roofline"] = {
-            "bound": "mfma", "kernel": "gemm_bf16_dma_kernel (all matrix products of one step; those of fewer than 384 tiles of 256x256 run as gemm_bf16_ring_kernel)",
+            "bound": "mfma", "kernel": "gemm_bf16_dma_kernel (all matrix products of one step; products of fewer than 384 tiles of 256x256, and the short last round of the products one column band wide, run as gemm_bf16_ring_kernel)",
             "achieved": achieved, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": achieved / PEAK_BF16_TFLOPS,
             # register-only MFMA loop on this device, TFLOP/s: operands random like real data / one constant
             "measured_mfma_ceiling": V.vit_mfma_ceiling(0, 0.1, True),
