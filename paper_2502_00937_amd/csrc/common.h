@@ -76,24 +76,24 @@ template <> struct Elem<bf16_t> {
 // Exact-form GELU z/2 (1 + erf(z / sqrt 2)).
 __device__ inline float gelu_erf(float z) { return 0.5f * z * (1.0f + erff(z * 0.70710678118654752440f)); }
 
-// GELU for the bf16 path, z/2 * (1 + erf(z / sqrt 2)), without transcendental instructions: with
-// t = min(|z|, 4), erf(t / sqrt 2) ~ t * P(t^2), P a degree-7 minimax polynomial constrained to
-// 4 * P(16) = 1 - 2e-6 (so the value never exceeds 1 and large |z| give z resp. 0 to 1e-6 relative).
-// |error| of the result <= 1.5e-4 for |z| <= 50 (about 3e-6 |z| beyond), largest near |z| = 3.8,
-// where the bf16 output's own rounding step is 1.6e-2.  The epilogue that applies it is bound by its VALU instructions: this
-// form costs 12 of them, the rational approximation on exp2 / rcp cost 14 plus two quarter-rate ones.
-__device__ inline float gelu_fast(float z) {
-  const float t = fminf(fabsf(z), 4.0f);
+// GELU for the bf16 path, z/2 * (1 + erf(z / sqrt 2)), without transcendental instructions, taking HALF its
+// argument (the epilogue forms h = z / 2 with the multiply-add that adds the bias): with t = min(|h|, 2),
+// erf(sqrt 2 h) ~ t * Q(t^2), Q a degree-6 minimax polynomial (weighted for the error of the product below)
+// constrained to 2 * Q(4) = 1 - 2e-6, so the value never exceeds 1 and large |z| give z resp. 0 to 3e-6 relative.
+// |error of the result| <= 1.9e-4 for |z| <= 50, largest near |z| = 3.9, where the bf16 output's own rounding
+// step is 1.6e-2.  The epilogue that applies it is bound by its VALU instructions: this form costs 10 of them
+// after the bias multiply-add; the rational approximation on exp2 / rcp cost 14 plus two quarter-rate ones.
+__device__ inline float gelu_fast_half(float h) {
+  const float t = fminf(fabsf(h), 2.0f);
   const float u = t * t;
-  float p = fmaf(-2.601771131e-09f, u, 2.115570961e-07f);
-  p = fmaf(p, u, -7.481196705e-06f);
-  p = fmaf(p, u, 1.531067693e-04f);
-  p = fmaf(p, u, -2.046607825e-03f);
-  p = fmaf(p, u, 1.917701427e-02f);
-  p = fmaf(p, u, -1.321476569e-01f);
-  p = fmaf(p, u, 7.976186126e-01f);
-  const float e = t * p;                    // erf(|z| / sqrt 2), in [0, 1)
-  return 0.5f * fmaf(fabsf(z), e, z);       // (z + |z| erf) / 2
+  float p = fmaf(3.698568902e-04f, u, -6.504944063e-03f);
+  p = fmaf(p, u, 4.889602571e-02f);
+  p = fmaf(p, u, -2.078860937e-01f);
+  p = fmaf(p, u, 5.608358441e-01f);
+  p = fmaf(p, u, -1.032848863e+00f);
+  p = fmaf(p, u, 1.591477259e+00f);
+  const float e = t * p;          // erf(|z| / sqrt 2), in [0, 1)
+  return fmaf(fabsf(h), e, h);    // (z + |z| erf) / 2
 }
 
 // ---- epilogues of the matrix products ---------------------------------------------------

@@ -99,12 +99,12 @@ __device__ __forceinline__ void wave_epilogue(const GemmArgs& a, f32x16 (&acc)[F
       __builtin_amdgcn_wave_barrier();
     }
   } else {  // EPI_BIAS, EPI_BIAS_GELU: bf16 output
-    float cs[FN][4];  // column scale of each accumulator quad (see GemmArgs::q_cols); the bias is scaled with it
+    float cs[FN][4];  // scale of each accumulator quad: the query columns' (see GemmArgs::q_cols), 1/2 ahead of GELU; the bias is scaled with it
 #pragma unroll
     for (int j = 0; j < FN; ++j)
 #pragma unroll
       for (int jj = 0; jj < 4; ++jj) {
-        cs[j][jj] = EPI == EPI_BIAS && ncol0 + j * 32 + jj * 8 + lk * 4 < a.q_cols ? a.q_scale : 1.0f;
+        cs[j][jj] = EPI == EPI_BIAS_GELU ? 0.5f : EPI == EPI_BIAS && ncol0 + j * 32 + jj * 8 + lk * 4 < a.q_cols ? a.q_scale : 1.0f;
         bias[j][jj] *= cs[j][jj];
       }
     unsigned char* st = smem + wave * 32 * STAGE_BF16;
@@ -120,7 +120,7 @@ __device__ __forceinline__ void wave_epilogue(const GemmArgs& a, f32x16 (&acc)[F
 #pragma unroll
           for (int e = 0; e < 4; ++e) {
             v[e] = fmaf(acc[i][j][jj * 4 + e], cs[j][jj], bias[j][jj][e]);
-            if constexpr (EPI == EPI_BIAS_GELU) v[e] = gelu_fast(v[e]);
+            if constexpr (EPI == EPI_BIAS_GELU) v[e] = gelu_fast_half(v[e]);
           }
           const u32x2 pk = {pack_bf16x2(v[0], v[1]), pack_bf16x2(v[2], v[3])};
           *(u32x2*)(st + lrow * STAGE_BF16 + (j * 32 + jj * 8 + lk * 4) * 2) = pk;
@@ -307,12 +307,12 @@ __device__ __forceinline__ void wave_epilogue_p(const GemmArgs& a, f32x16 (&acc)
   } else {  // EPI_BIAS, EPI_BIAS_GELU: bf16 output, pieces of 16 rows x 64 columns (128 bytes + pad)
     // (storing the 8-byte register quads directly was measured slower than this LDS round trip)
     // Store addresses: wave-uniform base (scalar arithmetic) + a per-lane byte offset that never changes.
-    float cs[FN][4];  // column scale of each accumulator quad (see GemmArgs::q_cols); the bias is scaled with it
+    float cs[FN][4];  // scale of each accumulator quad: the query columns' (see GemmArgs::q_cols), 1/2 ahead of GELU; the bias is scaled with it
 #pragma unroll
     for (int j = 0; j < FN; ++j)
 #pragma unroll
       for (int jj = 0; jj < 4; ++jj) {
-        cs[j][jj] = EPI == EPI_BIAS && ncol0 + j * 32 + jj * 8 + lk * 4 < a.q_cols ? a.q_scale : 1.0f;
+        cs[j][jj] = EPI == EPI_BIAS_GELU ? 0.5f : EPI == EPI_BIAS && ncol0 + j * 32 + jj * 8 + lk * 4 < a.q_cols ? a.q_scale : 1.0f;
         bias[j][jj] *= cs[j][jj];
       }
     const int sc = (lane & 7) * 8;
@@ -331,7 +331,7 @@ __device__ __forceinline__ void wave_epilogue_p(const GemmArgs& a, f32x16 (&acc)
 #pragma unroll
           for (int e = 0; e < 4; ++e) {
             v[e] = fmaf(acc[i][j][jj * 4 + e], cs[j][jj], bias[j][jj][e]);
-            if constexpr (EPI == EPI_BIAS_GELU) v[e] = gelu_fast(v[e]);
+            if constexpr (EPI == EPI_BIAS_GELU) v[e] = gelu_fast_half(v[e]);
           }
           pk[j][jj] = u32x2{pack_bf16x2(v[0], v[1]), pack_bf16x2(v[2], v[3])};
         }
