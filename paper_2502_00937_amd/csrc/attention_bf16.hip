@@ -59,9 +59,10 @@ struct AttnShape {
   static constexpr int V_ITEMS = (AKV / 2) * NCH;  // (key pair, chunk) items of the V tile
   static constexpr int K_PER = (K_ITEMS + ANT - 1) / ANT, V_PER = (V_ITEMS + ANT - 1) / ANT;
   // where the row sums of P come from in the fast pass: spare rows of the last O^T block if the head dim leaves
-  // any (72, 80), additions otherwise.  (One more accumulator fed by a fragment of ones held in registers costs
-  // 20 registers: at head dim 64 that is the fourth wave of a SIMD, and the kernel came out 5 % slower with it
-  // than with the additions, 13 % when forced into 128 registers.)
+  // any (72, 80), vector instructions otherwise (v_dot2c_f32_bf16 of a packed pair with a pair of ones: 8 per
+  // block of logits).  (One more accumulator fed by a fragment of ones held in registers costs 20 registers: at
+  // head dim 64 that is the fourth wave of a SIMD, and the kernel came out 5 % slower with it, 13 % when forced
+  // into 128 registers.)
   static constexpr int SUM = DB * 32 - DHP >= 8 ? SUM_ROWS : SUM_VALU;
 };
 
@@ -219,7 +220,8 @@ __global__ __launch_bounds__(64 * NW, QB == 1 ? (DHP == 64 ? 4 : DHP <= 96 ? 3 :
   // is checked once, after the last tile; a workgroup with a row outside runs the general pass instead.  Per
   // 32 x 32 block of logits this pass issues 16 exp2, 8 packed conversions and its MFMAs; the row sums come from
   // the matrix cores where the head dim leaves spare rows in the last O^T block (SUM_ROWS: two rows of ones in the
-  // V^T tile's padding), else from 16 additions (SUM_VALU).
+  // V^T tile's padding), else from 8 two-element dot products with ones (SUM_VALU).  Either way the sum is taken
+  // over the rounded weights, the ones the second product multiplies with.
   //
   // General pass: the online softmax with a lazily moving reference maximum m.  m only has to keep exp2 in range,
   // not to be the exact running maximum, so the row maximum is not computed on its common path either: a row sum
@@ -293,12 +295,20 @@ __global__ __launch_bounds__(64 * NW, QB == 1 ? (DHP == 64 ? 4 : DHP <= 96 ? 3 :
             for (int s2 = 0; s2 < 2; ++s2) {
               float p[8];
 #pragma unroll
-              for (int e = 0; e < 8; ++e) {
-                p[e] = __builtin_amdgcn_exp2f(FAST ? sq[s2 * 8 + e] : sq[s2 * 8 + e] + neg_m);
-                if (SUM == SUM_VALU) psum += p[e];
+              for (int e = 0; e < 8; ++e) p[e] = __builtin_amdgcn_exp2f(FAST ? sq[s2 * 8 + e] : sq[s2 * 8 + e] + neg_m);
+              const uint32_t pw[4] = {pack_bf16x2(p[0], p[1]), pack_bf16x2(p[2], p[3]), pack_bf16x2(p[4], p[5]),
+                                      pack_bf16x2(p[6], p[7])};
+              const u32x4 pk = {pw[0], pw[1], pw[2], pw[3]};
+              if (SUM == SUM_VALU) {
+                // the row sum is taken over the rounded weights, the ones the second product multiplies with, two
+                // per instruction: v_dot2c_f32_bf16 with a pair of ones (fp32 accumulation).  (The packed words are
+                // taken from the scalar array: cast from the elements of the vector `pk`, this compiler gave all
+                // four instructions the vector's first register.)
+                const bf16x2 ones = {(__bf16)1.0f, (__bf16)1.0f};
+#pragma unroll
+                for (int e = 0; e < 4; ++e)
+                  psum = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, pw[e]), ones, psum, false);
               }
-              const u32x4 pk = {pack_bf16x2(p[0], p[1]), pack_bf16x2(p[2], p[3]), pack_bf16x2(p[4], p[5]),
-                                pack_bf16x2(p[6], p[7])};
               pf[qb][s2] = __builtin_bit_cast(bf16x8, pk);
             }
           };
