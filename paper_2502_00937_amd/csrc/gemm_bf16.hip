@@ -841,21 +841,20 @@ hipError_t launch_gemm_bf16(const GemmArgs& a, hipStream_t s) {
   // 16-byte epilogue accesses need 8-element aligned columns and leading dimensions
   if (a.K <= 0 || a.K % BK != 0 || a.lda % 8 != 0 || a.ldw % 8 != 0 || a.ldo % 8 != 0 || a.N % 8 != 0)
     return hipErrorInvalidValue;
-  // The persistent 256 x 256 kernel pays off from about one and a half tiles per compute unit
-  // (measured crossover between 300 and 440 tiles on the encoder's shapes); below that its last,
-  // partly filled round costs more than the smaller tiles' extra operand traffic.
   const int tiles_m = (a.M + 255) / 256, tiles_n = (a.N + 255) / 256;
   const long big_tiles = (long)tiles_m * tiles_n;
-  if (big_tiles < 384) return launch_ring(a, s);
   // A product one column band wide (1, 2 or 4 tile columns) is walked in rounds of 256 / tiles_n row blocks, one
-  // tile per compute unit.  When the last round holds at most 64 tiles, three quarters or more of the units would
-  // sit out a whole tile time: those row blocks go to the small-tile kernel in a second launch instead (at most
-  // 256 tiles of 128 x 128, one short round).  Both kernels give a row the same bits, so where the cut falls does
-  // not show in the result.  The cut is made at the end the walk reaches last.
+  // tile per compute unit.  When the last round holds at most 128 tiles, half or more of the units would sit out a
+  // whole tile time: those row blocks go to the small-tile kernel in a second launch instead (at most 512 tiles of
+  // 128 x 128: one round of two workgroups per unit), also when that leaves the persistent kernel a single round
+  // (a product of 257 to 383 tiles, which as a whole would be too small for it).  Measured on the N = 1024
+  // products at 24 to 64 images: a limit of 64 tiles leaves 3 % on the table at 36 to 40 and at 64 images, a
+  // limit of 192 loses 5 % at 48.  Both kernels give a row the same bits, so where the cut falls does not show
+  // in the result.  The cut is made at the end the walk reaches last.
   if (a.epilogue != EPI_PATCH && (tiles_n == 1 || tiles_n == 2 || tiles_n == 4)) {
     const int per_round = 256 / tiles_n;
     const int tail_blocks = tiles_m % per_round;
-    if (tail_blocks > 0 && tiles_m > per_round && tail_blocks * tiles_n <= 64) {
+    if (tail_blocks > 0 && tiles_m > per_round && tail_blocks * tiles_n <= 128) {
       const int cut = a.reverse ? tail_blocks * 256 : (tiles_m - tail_blocks) * 256;  // first row of the upper part
       auto rows_from = [&](int row0, int rows) {
         GemmArgs b = a;
@@ -870,6 +869,10 @@ hipError_t launch_gemm_bf16(const GemmArgs& a, hipStream_t s) {
       return launch_ring(a.reverse ? lower : upper, s);
     }
   }
+  // The persistent 256 x 256 kernel pays off from about one and a half tiles per compute unit
+  // (measured crossover between 300 and 440 tiles on the encoder's shapes); below that its last,
+  // partly filled round costs more than the smaller tiles' extra operand traffic.
+  if (big_tiles < 384) return launch_ring(a, s);
   return launch_dma(a, s);
 }
 
