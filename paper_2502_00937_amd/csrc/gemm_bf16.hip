@@ -751,9 +751,12 @@ hipError_t launch_ring(const GemmArgs& a, hipStream_t s) {
   const int m_blocks = (mt_per_xcd + GROUP_M - 1) / GROUP_M;
   const long grid = 8L * m_blocks * n_bands * GROUP_M * GROUP_N;
   if (grid > 0x7fffffffL) return hipErrorInvalidValue;
-  // More tiles than compute units: two-stage rings (64 KiB) so that two workgroups share a unit and
-  // the rounds overlap; otherwise the four-stage ring, whose loads run three stages ahead.
-  const bool two = (long)tiles_m * tiles_n > 256;
+  // Up to one tile per compute unit: the four-stage ring, whose loads run three stages ahead.  Beyond that either
+  // two-stage rings (64 KiB), two workgroups to a unit covering each other's waits, in rounds of 512 tiles, or the
+  // four-stage ring in rounds of 256: a k-stage of a workgroup takes 0.95 us when it shares its unit and 0.58 us
+  // when it has it alone (measured on the N = 1024 products), so whichever needs fewer rounds by that measure.
+  const long n_tiles = (long)tiles_m * tiles_n;
+  const bool two = n_tiles > 256 && ((n_tiles + 511) / 512) * 95 < ((n_tiles + 255) / 256) * 58;
 #define VIT_LAUNCH_NS(EPI, NS, BM)                                                                                   \
   do {                                                                                                               \
     auto kfn = gemm_bf16_ring_kernel<EPI, NS, BM>;                                                                   \
