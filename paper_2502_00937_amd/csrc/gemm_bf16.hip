@@ -5,7 +5,8 @@
 //
 // Two kernels share the fragment layout and the epilogues; both move their operands global -> LDS
 // directly (global_load_lds_dwordx4) and are described where they are defined:
-// * gemm_bf16_ring_kernel (below 384 tiles of 256 x 256): one 128 x 128 (or 64 x 128) tile per workgroup, eight
+// * gemm_bf16_ring_kernel (below 384 tiles of 256 x 256, and short last rounds of the large kernel): one 128 x 128
+//   (or 64 x 128) tile per workgroup, eight
 //   waves of 64 x 32, a ring of four (or two) 64-wide k-stages;
 // * gemm_bf16_dma_kernel (everything large): persistent, 256 x 256 tiles, eight waves of 128 x 64,
 //   two 64-wide k-stages.
@@ -617,7 +618,8 @@ __global__ __launch_bounds__(512) void gemm_bf16_dma_kernel(const GemmArgs a, in
 }
 
 // ---------------------------------------------------------------------------------------------
-// Small-problem kernel (fewer than 384 tiles of 256 x 256): one 128 x 128 tile per workgroup, eight
+// Small-problem kernel (fewer than 384 tiles of 256 x 256; also the short last round of a large product that is
+// one column band wide, see launch_gemm_bf16): one 128 x 128 tile per workgroup, eight
 // waves of 64 x 32 (two per SIMD), operands global -> LDS directly into a ring of R_NS 64-wide
 // k-stages (32 KiB each).  One wait + barrier per stage establishes that the stage has landed for
 // every wave and that the slot refilled next is dead; all fragments of a stage are read before
@@ -625,8 +627,8 @@ __global__ __launch_bounds__(512) void gemm_bf16_dma_kernel(const GemmArgs a, in
 // * R_NS = 4 when there are no more tiles than compute units: a workgroup is then alone on its
 //   unit and nothing but its own instruction order hides latency, so the loads run three stages
 //   ahead.
-// * R_NS = 2 (64 KiB) otherwise: two workgroups share a unit and cover each other's waits, and a
-//   grid of 1.2 or 1.7 rounds no longer costs 2.
+// * R_NS = 2 (64 KiB) beyond that when it needs fewer rounds (see launch_ring): two workgroups share a unit
+//   and cover each other's waits, and a grid of 1.2 or 1.7 rounds no longer costs 2.
 // (The register-staged predecessor spent 2 800 clocks per k-stage on 512 clocks of MFMA work: LDS
 // writes, their waits and un-overlapped fragment reads.)
 // * BM = 64 (a 64 x 128 tile, waves of 32 x 32, 24 KiB stages) for the very smallest products, one or two
