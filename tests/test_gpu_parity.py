@@ -246,7 +246,11 @@ def test_one_handle_serves_batches_of_changing_size_without_waiting():
         want, _ = fresh.encode(px[:int(to[-1])], [len(tpi)], to)
         torch.cuda.synchronize()
         fresh.close()
-        assert torch.equal(g, want), tpi[:4]
+        if not torch.equal(g, want):  # say where: a stale buffer, a lost tile and a stray write look different
+            d = (g.float() - want.float()).abs().max(1).values
+            rows = torch.nonzero(d > 0).flatten().tolist()
+            raise AssertionError(f"batch {tpi[:4]}... ({sum(tpi)} tiles): {len(rows)} of {g.shape[0]} token rows differ, "
+                                 f"first {rows[:8]}, last {rows[-3:]}, largest difference {float(d.max()):.3e}")
 
 
 def test_profile_counters():
