@@ -175,9 +175,6 @@ constexpr int D_STAGE_BYTES = (D_BM + D_BN) * D_ROW;  // 64 KiB
 constexpr int D_STAGING_ROW = 144, D_STAGING_BYTES = 8 * 16 * D_STAGING_ROW;
 constexpr int D_LDS_BYTES = D_ST * D_STAGE_BYTES + D_STAGING_BYTES;  // 146 KiB of the 160 KiB
 constexpr int D_GROUP_M = 8, D_GROUP_N = 4;
-#ifndef VIT_RESID_PD
-#define VIT_RESID_PD 4
-#endif
 constexpr int D_LOADS = 8;  // direct-to-LDS instructions per wave and stage (4 for A, 4 for W), 8 rows each
 
 typedef const __attribute__((address_space(1))) void* gptr_t;
