@@ -106,6 +106,36 @@ def test_odd_k_stage_counts_and_narrow_column_bands_on_the_persistent_gemm():
     assert got.shape[0] == 500 * 197
 
 
+def test_short_last_rounds_of_one_and_two_column_products():
+    """The same network at 390 tiles (76 830 rows, 301 row blocks).  The products one tile column wide are walked in
+    rounds of 256 row blocks and those two columns wide in rounds of 128; both leave 45 row blocks for a last round
+    that would idle most of the device, so those rows go to the ring kernel in a launch of their own (at either end
+    of the matrix: the walk alternates its direction from one product to the next).  The oracle encodes the first
+    image, one inside and the last; the first and last two images encoded alone (ring kernel only) must give the
+    bits they have in the batch."""
+    import torch
+
+    import paper_2502_00937_amd as V
+
+    cfg = gen.get_config("test_oddk_bf16")
+    tpi = [1] * 390
+    say("case short last rounds (390 tiles, persistent + ring launches per product)")
+    got, _ = check_case(cfg, tpi, [len(tpi)], images=[0, 200, 389], label="short-round")
+    assert got.shape[0] == 390 * 197
+    enc = V.VitEncoder(cfg, gen.make_weights(cfg, seed=0), device=0)
+    try:
+        px = torch.from_numpy(gen.make_pixels(cfg, 390, seed=1)).cuda()
+        full, _ = enc.encode(px, [390], np.arange(391, dtype=np.int32))
+        for lo in (0, 388):
+            part, _ = enc.encode(px[lo:lo + 2], [2], np.arange(3, dtype=np.int32))
+            torch.cuda.synchronize()
+            same = torch.equal(part.view(torch.int16), full[lo * 197:(lo + 2) * 197].view(torch.int16))
+            say(f"    images {lo}, {lo + 1} alone against the batch: bit-identical = {same}")
+            assert same
+    finally:
+        enc.close()
+
+
 def test_odd_k_stage_counts_on_the_ring_gemm():
     """The same network at 60 tiles (11 820 rows, 47 row blocks): every product takes the ring kernel, with
     1, 3 and 5 k-stages (fewer than the ring is deep) and rings of four and of two stages."""
