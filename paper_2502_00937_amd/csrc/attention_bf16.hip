@@ -57,6 +57,14 @@ struct AttnShape {
   static constexpr int STAGE = K_BYTES + VT_BYTES;
   static constexpr int K_ITEMS = AKV * NCH;        // 16-byte chunks of the K tile
   static constexpr int V_ITEMS = (AKV / 2) * NCH;  // (key pair, chunk) items of the V tile
+  // Item -> (key pair, chunk): blocks of 32 key pairs x CW chunks, the chunk running fastest.  With CW = 4 one load
+  // instruction covers 16 key pairs x 64 bytes where CW = 1 covers 32 x 32 bytes, half the cache lines per
+  // instruction for the unit that turns lane addresses into cache requests (3 % of the kernel), and a half wave's
+  // transposed stores (bank = 16 * chunk + key pair + const) still fall on 32 different banks; with CW = 8 (whole
+  // 128-byte rows per instruction) they collide two by two and the kernel is 4 % slower than with 4: measured.
+  static constexpr int CW = NCH % 4 == 0 ? 4 : NCH % 2 == 0 ? 2 : 1;
+  static __device__ __forceinline__ int v_kp(int it) { return (it % (32 * CW)) / CW; }
+  static __device__ __forceinline__ int v_ch(int it) { return (it / (32 * CW)) * CW + it % CW; }
   static constexpr int K_PER = (K_ITEMS + ANT - 1) / ANT, V_PER = (V_ITEMS + ANT - 1) / ANT;
   // where the row sums of P come from in the fast pass: spare rows of the last O^T block if the head dim leaves
   // any (72, 80), vector instructions otherwise (v_dot2c_f32_bf16 of a packed pair with a pair of ones: 8 per
@@ -83,8 +91,13 @@ __global__ __launch_bounds__(64 * NW, QB == 1 ? (DHP == 64 ? 4 : DHP <= 96 ? 3 :
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int lq = lane & 31, g = lane >> 5;
   const int partner_addr = (lane ^ 32) << 2;  // ds_bpermute byte address of the lane that holds the other 16 keys of a query
-  const bf16_t* base = (const bf16_t*)a.qkv;
-  const int qoff = head * DHP, koff = (a.heads + head) * DHP, voff = (2 * a.heads + head) * DHP;
+  // this head's Q, K and V: column blocks of the [rows, ld_qkv] matrix, or (qkv_rows != 0) blocks of their own,
+  // [qkv_rows, DHP] each with consecutive rows.  Either way: a base and a row stride.
+  const size_t blk = a.qkv_rows ? a.qkv_rows * DHP : (size_t)DHP;  // elements from one head's block to the next
+  const int row_elems = a.qkv_rows ? DHP : a.ld_qkv;
+  const bf16_t* q_base = (const bf16_t*)a.qkv + (size_t)head * blk;
+  const bf16_t* k_base = (const bf16_t*)a.qkv + (size_t)(a.heads + head) * blk;
+  const bf16_t* v_base = (const bf16_t*)a.qkv + (size_t)(2 * a.heads + head) * blk;
   const int seg_end = w.seg_start + w.seg_len;
 
   // Q^T fragments of the wave's two query blocks: lane holds d = 16*ks + 8*g .. +8 of its query row;
@@ -96,9 +109,9 @@ __global__ __launch_bounds__(64 * NW, QB == 1 ? (DHP == 64 ? 4 : DHP <= 96 ? 3 :
 #pragma unroll
     for (int ks = 0; ks < Sh::KS; ++ks) {
       if (ks * 16 + 8 < DHP) {  // both 8-wide halves of the k-step lie inside the head
-        qf[qb][ks] = *(const bf16x8*)(base + (size_t)qload * a.ld_qkv + qoff + ks * 16 + g * 8);
+        qf[qb][ks] = *(const bf16x8*)(q_base + (size_t)qload * row_elems + ks * 16 + g * 8);
       } else {  // head dim 72: the upper half of the last k-step does not exist; its lanes feed zeros
-        const bf16x8 lo = *(const bf16x8*)(base + (size_t)qload * a.ld_qkv + qoff + ks * 16);
+        const bf16x8 lo = *(const bf16x8*)(q_base + (size_t)qload * row_elems + ks * 16);
         const u32x4 z = {0u, 0u, 0u, 0u};
         qf[qb][ks] = g == 0 ? lo : __builtin_bit_cast(bf16x8, z);
       }
@@ -109,8 +122,9 @@ __global__ __launch_bounds__(64 * NW, QB == 1 ? (DHP == 64 ? 4 : DHP <= 96 ? 3 :
   // global -> registers.  Each thread's (row, column) inside a tile is fixed, so its byte offsets
   // are computed once; only a segment's last tile clamps rows past the end to the last row (their
   // logits are masked, the clamped values only need to be finite).
-  const unsigned char* seg_base = (const unsigned char*)(base + (size_t)w.seg_start * a.ld_qkv);
-  const uint32_t row_bytes = (uint32_t)a.ld_qkv * 2u;
+  const uint32_t row_bytes = (uint32_t)row_elems * 2u;
+  const unsigned char* seg_k = (const unsigned char*)(k_base + (size_t)w.seg_start * row_elems);
+  const unsigned char* seg_v = (const unsigned char*)(v_base + (size_t)w.seg_start * row_elems);
   // Each thread's (row, column) inside a tile is fixed: its byte offsets from the tile's first row are
   // computed once, and a full tile is loaded from a wave-uniform base plus those offsets with no
   // address arithmetic at all.  Only a segment's last, partial tile clamps rows past the end to the
@@ -121,16 +135,17 @@ __global__ __launch_bounds__(64 * NW, QB == 1 ? (DHP == 64 ? 4 : DHP <= 96 ? 3 :
   //  store it: no load sits under divergent control flow)
   for (int i = 0; i < Sh::K_PER; ++i) {
     const int it = min(tid + i * ANT, Sh::K_ITEMS - 1), key = it / Sh::NCH;
-    k_off[i] = (uint32_t)key * row_bytes + (uint32_t)(koff + (it - key * Sh::NCH) * 8) * 2u;
+    k_off[i] = (uint32_t)key * row_bytes + (uint32_t)((it - key * Sh::NCH) * 8) * 2u;
   }
 #pragma unroll
   for (int i = 0; i < Sh::V_PER; ++i) {
     const int it = min(tid + i * ANT, Sh::V_ITEMS - 1);
-    v_off[i] = (uint32_t)(2 * (it & 31)) * row_bytes + (uint32_t)(voff + (it >> 5) * 8) * 2u;
+    v_off[i] = (uint32_t)(2 * Sh::v_kp(it)) * row_bytes + (uint32_t)(Sh::v_ch(it) * 8) * 2u;
   }
   auto load_tile = [&](int k0, auto partial_tag) {
     constexpr bool PARTIAL = decltype(partial_tag)::value;
-    const unsigned char* tile_base = seg_base + (size_t)k0 * row_bytes;  // wave-uniform
+    const unsigned char* tile_k = seg_k + (size_t)k0 * row_bytes;  // wave-uniform
+    const unsigned char* tile_v = seg_v + (size_t)k0 * row_bytes;
     const int last = w.seg_len - 1 - k0;  // largest valid row index inside this tile (>= 0)
 #pragma unroll
     for (int i = 0; i < Sh::K_PER; ++i) {
@@ -140,19 +155,19 @@ __global__ __launch_bounds__(64 * NW, QB == 1 ? (DHP == 64 ? 4 : DHP <= 96 ? 3 :
         const int key = it / Sh::NCH;
         off -= (uint32_t)(key - min(key, last)) * row_bytes;
       }
-      rk[i] = *(const u32x4*)(tile_base + off);
+      rk[i] = *(const u32x4*)(tile_k + off);
     }
 #pragma unroll
     for (int i = 0; i < Sh::V_PER; ++i) {
       const int it = min(tid + i * ANT, Sh::V_ITEMS - 1);
       uint32_t o0 = v_off[i], o1 = v_off[i] + row_bytes;
       if (PARTIAL) {
-        const int r = 2 * (it & 31);
+        const int r = 2 * Sh::v_kp(it);
         o0 -= (uint32_t)(r - min(r, last)) * row_bytes;
         o1 -= (uint32_t)(r + 1 - min(r + 1, last)) * row_bytes;
       }
-      rv0[i] = *(const u32x4*)(tile_base + o0);
-      rv1[i] = *(const u32x4*)(tile_base + o1);
+      rv0[i] = *(const u32x4*)(tile_v + o0);
+      rv1[i] = *(const u32x4*)(tile_v + o1);
     }
   };
   // registers -> LDS; V is transposed on the way in: V^T[d][2kp], V^T[d][2kp+1] packed into one word
@@ -169,7 +184,7 @@ __global__ __launch_bounds__(64 * NW, QB == 1 ? (DHP == 64 ? 4 : DHP <= 96 ? 3 :
     for (int i = 0; i < Sh::V_PER; ++i) {
       const int it = tid + i * ANT;
       if (Sh::V_ITEMS % ANT == 0 || it < Sh::V_ITEMS) {
-        const int ch = it >> 5, kp = it & 31;
+        const int ch = Sh::v_ch(it), kp = Sh::v_kp(it);
 #pragma unroll
         for (int e = 0; e < 4; ++e) {
           const uint32_t x0 = rv0[i][e], x1 = rv1[i][e];  // v_perm_b32: bytes 0-3 = x0, 4-7 = x1
@@ -411,7 +426,7 @@ int attention_q_block(int dtype_bf16, int dh_pad) { return !dtype_bf16 ? 64 : 12
 
 hipError_t launch_attention_bf16(const AttnArgs& a, hipStream_t s) {
   if (a.n_work <= 0) return hipSuccess;
-  if (a.ld_qkv % 8 != 0 || a.ld_o % 4 != 0) return hipErrorInvalidValue;
+  if ((a.qkv_rows == 0 && a.ld_qkv % 8 != 0) || a.ld_o % 4 != 0) return hipErrorInvalidValue;
   const dim3 grid(((a.n_work + 7) / 8) * 8, a.heads);
 #define VIT_ATTN(DHP, QB, NW)                                                                            \
   do {                                                                                                 \

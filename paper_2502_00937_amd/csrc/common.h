@@ -101,7 +101,8 @@ enum Epilogue {
   EPI_BIAS = 0,           // out[r, c] = acc + bias[c]                         (activation type)
   EPI_BIAS_GELU = 1,      // out[r, c] = gelu(acc + bias[c])                   (activation type)
   EPI_BIAS_RESIDUAL = 2,  // resid[r, c] += acc + bias[c]                      (fp32, in place)
-  EPI_PATCH = 3           // resid[tile*T + cls + patch, c] = acc + bias[c] + pos[cls + patch, c]
+  EPI_PATCH = 3,          // resid[tile*T + cls + patch, c] = acc + bias[c] + pos[cls + patch, c]
+  EPI_BIAS_HEADS = 4      // bf16 only: EPI_BIAS with the output laid out head by head (GemmArgs::hm_dh)
 };
 
 struct GemmArgs {
@@ -122,9 +123,12 @@ struct GemmArgs {
   int reverse;        // 1: walk the row blocks from the last to the first (see vit_encode_packed)
   unsigned long long* tile_stamps;  // measurement aid, normally null: [256 workgroups][kTileStampSlots][4] words written
                                     // by the persistent kernel per tile (see vit_profile_tiles_read)
-  int q_cols;         // EPI_BIAS: output columns [0, q_cols) are multiplied by q_scale after the bias (0: none);
+  int q_cols;         // EPI_BIAS, EPI_BIAS_HEADS: output columns [0, q_cols) are multiplied by q_scale after the bias (0: none);
   float q_scale;      //   the QKV product hands the attention kernel its queries times log2(e) / sqrt(head dim)
   int stream_out;     // 1: the bf16 output exceeds the memory-side cache; the persistent kernel stores it non-temporally
+  int hm_dh;          // EPI_BIAS_HEADS: 64 or 128; the output is laid out head by head, column c of row r at
+  size_t hm_rows;     //   ((c / hm_dh) * hm_rows + r) * hm_dh + c % hm_dh (every head's rows contiguous: what the
+                      //   attention kernel reads); ldo is not used
 };
 
 // Applies one epilogue to a single accumulator; the caller guarantees row < M and col < N.
@@ -155,7 +159,10 @@ struct AttnWork {
 };
 
 struct AttnArgs {
-  const void* qkv;  // [rows, ld_qkv]: Q heads, then K heads, then V heads, each head dh_pad wide
+  const void* qkv;  // qkv_rows == 0: [rows, ld_qkv], Q heads, then K heads, then V heads, each head dh_pad wide;
+                    // else (bf16 path, head dims 64 and 128) the same 3 * heads column blocks laid out one after
+                    // the other, each [qkv_rows, dh_pad] (GemmArgs::hm_dh): a head's keys are consecutive rows
+  size_t qkv_rows;  // rows of each head's block, or 0
   void* out;        // [rows, ld_o]: head h at columns h*dh_pad
   const AttnWork* work;
   int n_work;

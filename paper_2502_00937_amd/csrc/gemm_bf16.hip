@@ -105,12 +105,18 @@ __device__ __forceinline__ void wave_epilogue(const GemmArgs& a, f32x16 (&acc)[F
     for (int j = 0; j < FN; ++j)
 #pragma unroll
       for (int jj = 0; jj < 4; ++jj) {
-        cs[j][jj] = EPI == EPI_BIAS_GELU ? 0.5f : EPI == EPI_BIAS && ncol0 + j * 32 + jj * 8 + lk * 4 < a.q_cols ? a.q_scale : 1.0f;
+        cs[j][jj] = EPI == EPI_BIAS_GELU ? 0.5f : ncol0 + j * 32 + jj * 8 + lk * 4 < a.q_cols ? a.q_scale : 1.0f;
         bias[j][jj] *= cs[j][jj];
       }
     unsigned char* st = smem + wave * 32 * STAGE_BF16;
     constexpr int LPR = TN / 8;  // lanes per staged row (16 bytes = 8 bf16 each)
     constexpr int RPI = 64 / LPR;
+    // EPI_BIAS_HEADS: heads of 64 or 128 columns stored one after the other, so the wave's TN columns lie inside
+    // one head: a row stride and the offset of column ncol0, both wave-uniform
+    const int hm_blk = EPI == EPI_BIAS_HEADS ? ncol0 / a.hm_dh : 0;
+    const int rs = EPI == EPI_BIAS_HEADS ? a.hm_dh : a.ldo;
+    const size_t col0_off =
+        EPI == EPI_BIAS_HEADS ? (size_t)hm_blk * a.hm_rows * a.hm_dh + (ncol0 - hm_blk * a.hm_dh) : (size_t)ncol0;
 #pragma unroll
     for (int i = 0; i < FM; ++i) {
 #pragma unroll
@@ -132,7 +138,7 @@ __device__ __forceinline__ void wave_epilogue(const GemmArgs& a, f32x16 (&acc)[F
         const int sr = p * RPI + lane / LPR, sc = (lane % LPR) * 8;
         const int row = row0 + i * 32 + sr, col = ncol0 + sc;
         const u32x4 v = *(const u32x4*)(st + sr * STAGE_BF16 + sc * 2);
-        if (row < a.M && col < a.N) *(u32x4*)((bf16_t*)a.out + (size_t)row * a.ldo + col) = v;
+        if (row < a.M && col < a.N) *(u32x4*)((bf16_t*)a.out + (size_t)row * rs + col0_off + sc) = v;
       }
       __builtin_amdgcn_wave_barrier();
     }
@@ -188,7 +194,7 @@ __device__ __forceinline__ void wave_epilogue_p(const GemmArgs& a, f32x16 (&acc)
   constexpr int FM = 4, FN = 2;
   const int lrow = lane & 31, lk = lane >> 5;
   f32x4 bias[FN][4];  // per accumulator quad (the fp32 paths add their bias after the LDS round trip instead)
-  if constexpr (EPI == EPI_BIAS || EPI == EPI_BIAS_GELU) {
+  if constexpr (EPI == EPI_BIAS || EPI == EPI_BIAS_GELU || EPI == EPI_BIAS_HEADS) {
 #pragma unroll
     for (int j = 0; j < FN; ++j)
 #pragma unroll
@@ -310,12 +316,18 @@ __device__ __forceinline__ void wave_epilogue_p(const GemmArgs& a, f32x16 (&acc)
     for (int j = 0; j < FN; ++j)
 #pragma unroll
       for (int jj = 0; jj < 4; ++jj) {
-        cs[j][jj] = EPI == EPI_BIAS_GELU ? 0.5f : EPI == EPI_BIAS && ncol0 + j * 32 + jj * 8 + lk * 4 < a.q_cols ? a.q_scale : 1.0f;
+        cs[j][jj] = EPI == EPI_BIAS_GELU ? 0.5f : ncol0 + j * 32 + jj * 8 + lk * 4 < a.q_cols ? a.q_scale : 1.0f;
         bias[j][jj] *= cs[j][jj];
       }
     const int sc = (lane & 7) * 8;
-    const uint32_t lane_off = (uint32_t)((lane >> 3) * a.ldo + sc) * 2u;
-    unsigned char* const tile_base = (unsigned char*)a.out + ((size_t)row0 * a.ldo + ncol0) * 2;
+    // EPI_BIAS_HEADS: heads of 64 or 128 columns stored one after the other, so the wave's 64 columns lie inside one
+    // head: its rows are hm_dh elements apart and (row0, ncol0) sits at a wave-uniform address of its own
+    const int rs = EPI == EPI_BIAS_HEADS ? a.hm_dh : a.ldo;
+    const uint32_t lane_off = (uint32_t)((lane >> 3) * rs + sc) * 2u;
+    const int hm_blk = EPI == EPI_BIAS_HEADS ? ncol0 / a.hm_dh : 0;
+    unsigned char* const tile_base =
+        (unsigned char*)a.out + (EPI == EPI_BIAS_HEADS ? ((size_t)hm_blk * a.hm_rows + row0) * a.hm_dh + (ncol0 - hm_blk * a.hm_dh)
+                                                       : (size_t)row0 * a.ldo + ncol0) * 2;
     const int row_lim = a.M - row0 - (lane >> 3);
     const bool col_ok = ncol0 + sc < a.N;
 #pragma unroll
@@ -348,7 +360,7 @@ __device__ __forceinline__ void wave_epilogue_p(const GemmArgs& a, f32x16 (&acc)
           const int sr = p * 8 + (lane >> 3);
           const u32x4 t = *(const u32x4*)(st + sr * D_STAGING_ROW + sc * 2);
           if (FULL || (i * 32 + half * 16 + p * 8 < row_lim && col_ok)) {
-            u32x4* dst = (u32x4*)(tile_base + (size_t)(i * 32 + half * 16 + p * 8) * a.ldo * 2 + lane_off);
+            u32x4* dst = (u32x4*)(tile_base + (size_t)(i * 32 + half * 16 + p * 8) * rs * 2 + lane_off);
             // STREAM_OUT: the output is larger than the memory-side cache; it passes through once and
             // would only displace the operands, so it is stored non-temporally (-1 % on the large encode
             // step).  Smaller outputs are what the next kernel finds in that cache; there the hint costs
@@ -775,6 +787,7 @@ hipError_t launch_ring(const GemmArgs& a, hipStream_t s) {
   } while (0)
   switch (a.epilogue) {
     case EPI_BIAS: VIT_LAUNCH(EPI_BIAS); break;
+    case EPI_BIAS_HEADS: VIT_LAUNCH(EPI_BIAS_HEADS); break;
     case EPI_BIAS_GELU: VIT_LAUNCH(EPI_BIAS_GELU); break;
     case EPI_BIAS_RESIDUAL: VIT_LAUNCH(EPI_BIAS_RESIDUAL); break;
     case EPI_PATCH: VIT_LAUNCH(EPI_PATCH); break;
@@ -822,6 +835,10 @@ hipError_t launch_dma(const GemmArgs& a, hipStream_t s) {
       if (a.stream_out) VIT_LAUNCH(EPI_BIAS, true);
       else VIT_LAUNCH(EPI_BIAS, false);
       break;
+    case EPI_BIAS_HEADS:
+      if (a.stream_out) VIT_LAUNCH(EPI_BIAS_HEADS, true);
+      else VIT_LAUNCH(EPI_BIAS_HEADS, false);
+      break;
     case EPI_BIAS_GELU:
       if (a.stream_out) VIT_LAUNCH(EPI_BIAS_GELU, true);
       else VIT_LAUNCH(EPI_BIAS_GELU, false);
@@ -843,6 +860,8 @@ hipError_t launch_gemm_bf16(const GemmArgs& a, hipStream_t s) {
   // 16-byte epilogue accesses need 8-element aligned columns and leading dimensions
   if (a.K <= 0 || a.K % BK != 0 || a.lda % 8 != 0 || a.ldw % 8 != 0 || a.ldo % 8 != 0 || a.N % 8 != 0)
     return hipErrorInvalidValue;
+  // head-by-head output: heads of 64 or 128 columns (a wave's column block never straddles two)
+  if (a.epilogue == EPI_BIAS_HEADS && (a.hm_dh <= 0 || a.hm_dh % 64 != 0 || a.hm_rows < (size_t)a.M)) return hipErrorInvalidValue;
   const int tiles_m = (a.M + 255) / 256, tiles_n = (a.N + 255) / 256;
   const long big_tiles = (long)tiles_m * tiles_n;
   // A product one column band wide (1, 2 or 4 tile columns) is walked in rounds of 256 / tiles_n row blocks, one
@@ -862,7 +881,7 @@ hipError_t launch_gemm_bf16(const GemmArgs& a, hipStream_t s) {
         GemmArgs b = a;
         b.M = rows;
         b.A = (const unsigned char*)a.A + (size_t)row0 * a.lda * 2;
-        if (a.out) b.out = (unsigned char*)a.out + (size_t)row0 * a.ldo * 2;
+        if (a.out) b.out = (unsigned char*)a.out + (size_t)row0 * (a.epilogue == EPI_BIAS_HEADS ? a.hm_dh : a.ldo) * 2;  // a row's stride
         if (a.resid) b.resid = a.resid + (size_t)row0 * a.ldo;
         return b;
       };

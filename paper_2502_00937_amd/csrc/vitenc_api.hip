@@ -693,6 +693,14 @@ static vit_status_t encode_impl(const char* fn, vit_encoder_t* e, const float* p
       // the bf16 attention kernel takes its queries in units of log2: exp2(q . k) is the softmax weight
       a.q_cols = d.H * d.dhp;
       a.q_scale = 1.4426950408889634f / sqrtf((float)d.dh);
+      // and, for head dims whose rows are whole 128-byte lines, reads every head's rows back to back: the product's
+      // 3 * H column blocks are stored one after the other (rows of one head 6 KiB apart fall on a few sets of a
+      // compute unit's L1)
+      if (d.dhp % 64 == 0) {
+        a.epilogue = EPI_BIAS_HEADS;
+        a.hm_dh = d.dhp;
+        a.hm_rows = w.Mpad;
+      }
     }
     a.tile_stamps = e->tile_stamps && timing ? e->tile_stamps + (size_t)family * kStampWordsPerFamily : nullptr;
     ProfScope ps(e, s, family, timing);
@@ -723,7 +731,7 @@ static vit_status_t encode_impl(const char* fn, vit_encoder_t* e, const float* p
     {
       const bool global = l >= d.L_loc;
       AttnArgs a;
-      a.qkv = qkv; a.out = o;
+      a.qkv = qkv; a.out = o; a.qkv_rows = d.bf16 && d.dhp % 64 == 0 ? (size_t)w.Mpad : 0;
       a.work = global ? tables + w.max_work : tables;
       a.n_work = global ? n_global : n_local;
       a.heads = d.H; a.dh = d.dh; a.dh_pad = d.dhp; a.ld_qkv = d.QKVN; a.ld_o = d.Op;
