@@ -694,8 +694,9 @@ static vit_status_t encode_impl(const char* fn, vit_encoder_t* e, const float* p
       a.q_cols = d.H * d.dhp;
       a.q_scale = 1.4426950408889634f / sqrtf((float)d.dh);
       // and, for head dims whose rows are whole 128-byte lines, reads every head's rows back to back: the product's
-      // 3 * H column blocks are stored one after the other (rows of one head 6 KiB apart fall on a few sets of a
-      // compute unit's L1)
+      // 3 * H column blocks are stored one after the other, so a K or V tile is one contiguous block and not 64
+      // pieces a whole row of the product apart (an odd number of lines between the rows instead, which spreads
+      // them over the sets of a compute unit's L1 just as well, was measured to give nothing: it is the contiguity)
       if (d.dhp % 64 == 0) {
         a.epilogue = EPI_BIAS_HEADS;
         a.hm_dh = d.dhp;
