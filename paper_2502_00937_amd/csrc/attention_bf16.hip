@@ -399,11 +399,11 @@ __global__ __launch_bounds__(64 * NW, QB == 1 ? (DHP == 64 ? 4 : DHP <= 96 ? 3 :
 
   // ---- normalise and store: lane owns a query; registers 4j..4j+3 of block b are
   //      d = 32b + 8j + 4g .. +3, four consecutive columns -> one 8-byte piece.
-  // Head dims 64 and 128 (a head's row is whole 128-byte lines): the wave passes its 32 rows through LDS (free after
-  // the last tile's barrier; rows 8 bytes longer than the head, so the 8-byte writes of 16 rows and the read-back fall
-  // on different banks) and stores them 16 bytes per lane, eight or sixteen lanes per row: a store instruction then
-  // touches 8 or 4 rows where the direct 8-byte stores touch 32, a quarter of the cache requests for the same bytes.
-  if constexpr (DHP % 64 == 0 && QB == 1) {
+  // The wave passes its 32 rows through LDS (free after the last tile's barrier; rows 8 bytes longer than the head,
+  // so the 8-byte writes of 16 rows and the read-back fall on different banks) and stores them 16 bytes per lane,
+  // DHP / 8 lanes per row: a store instruction then touches 4 to 8 rows where direct 8-byte stores touch 32, a
+  // quarter of the cache requests for the same bytes.
+  if constexpr (QB == 1) {
     if (wave_active) {
       constexpr int ROWB = DHP * 2 + 8, NCH = DHP / 8;
       unsigned char* so = lds + wave * 32 * ROWB;
@@ -412,6 +412,7 @@ __global__ __launch_bounds__(64 * NW, QB == 1 ? (DHP == 64 ? 4 : DHP <= 96 ? 3 :
       for (int b = 0; b < Sh::DB; ++b)
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
+          if (b * 32 + 8 * j >= DHP) continue;  // the spare rows of the last O^T block
           const u32x2 pk = {pack_bf16x2(o[0][b][4 * j] * inv, o[0][b][4 * j + 1] * inv),
                             pack_bf16x2(o[0][b][4 * j + 2] * inv, o[0][b][4 * j + 3] * inv)};
           *(u32x2*)(so + lq * ROWB + (b * 32 + 8 * j + 4 * g) * 2) = pk;
@@ -419,10 +420,11 @@ __global__ __launch_bounds__(64 * NW, QB == 1 ? (DHP == 64 ? 4 : DHP <= 96 ? 3 :
       __builtin_amdgcn_wave_barrier();
       bf16_t* obase = (bf16_t*)a.out + (size_t)(w.q0 + wave * 32) * a.ld_o + head * DHP;
 #pragma unroll
-      for (int p = 0; p < 32 * NCH / 64; ++p) {
-        const int item = p * 64 + lane, row = item / NCH, ch = item % NCH;
+      for (int p = 0; p < (32 * NCH + 63) / 64; ++p) {
+        const int item = min(p * 64 + lane, 32 * NCH - 1), row = item / NCH, ch = item % NCH;
         const u32x2 lo = *(const u32x2*)(so + row * ROWB + ch * 16), hi = *(const u32x2*)(so + row * ROWB + ch * 16 + 8);
-        if (w.q0 + wave * 32 + row < seg_end) *(u32x4*)(obase + (size_t)row * a.ld_o + ch * 8) = u32x4{lo[0], lo[1], hi[0], hi[1]};
+        if (p * 64 + lane < 32 * NCH && w.q0 + wave * 32 + row < seg_end)
+          *(u32x4*)(obase + (size_t)row * a.ld_o + ch * 8) = u32x4{lo[0], lo[1], hi[0], hi[1]};
       }
     }
     return;
