@@ -753,8 +753,15 @@ hipError_t launch_ring(const GemmArgs& a, hipStream_t s) {
   const int tiles_n = (a.N + R_BN - 1) / R_BN;
   // At most 96 tiles of 128 x 128 (the N = 1024 products of one or two images): 64-row tiles, still fewer
   // workgroups than units.  Measured at 577 and 1154 rows: 40 and 80 tiles gain 30-45 %, 120 tiles (QKV of
-  // one image) lose 15 %.
-  const bool half = (long)((a.M + 127) / 128) * tiles_n <= 96;
+  // one image) lose 15 %.  Products of at most eight tile columns (N <= 1024) keep gaining up to one 64-row tile
+  // per unit (three images: 112 tiles of 128 rows, 224 of 64: out-proj and fc2 18-22 % faster), and again where
+  // the 128-row tiles are a few more than the units and their second workgroups leave most units with one: there
+  // three 64-row workgroups with two-stage rings share a unit in a single round of up to 768 tiles (eight images,
+  // 296 tiles of 128 rows: 7 %).
+  const long tiles128 = (long)((a.M + 127) / 128) * tiles_n, tiles64 = (long)((a.M + 63) / 64) * tiles_n;
+  const bool narrow = tiles_n <= 8;
+  const bool half3 = narrow && tiles128 > 256 && tiles64 <= 768;  // three two-stage workgroups of 64 rows per unit
+  const bool half = tiles128 <= 96 || (narrow && tiles64 <= 256) || half3;
   const int bm = half ? 64 : 128;
   const int tiles_m = (a.M + bm - 1) / bm;
   const int mt_per_xcd = (tiles_m + 7) / 8;
@@ -767,7 +774,7 @@ hipError_t launch_ring(const GemmArgs& a, hipStream_t s) {
   // four-stage ring in rounds of 256: a k-stage of a workgroup takes 0.95 us when it shares its unit and 0.58 us
   // when it has it alone (measured on the N = 1024 products), so whichever needs fewer rounds by that measure.
   const long n_tiles = (long)tiles_m * tiles_n;
-  const bool two = n_tiles > 256 && ((n_tiles + 511) / 512) * 95 < ((n_tiles + 255) / 256) * 58;
+  const bool two = !half && n_tiles > 256 && ((n_tiles + 511) / 512) * 95 < ((n_tiles + 255) / 256) * 58;
 #define VIT_LAUNCH_NS(EPI, NS, BM)                                                                                   \
   do {                                                                                                               \
     auto kfn = gemm_bf16_ring_kernel<EPI, NS, BM>;                                                                   \
@@ -778,7 +785,9 @@ hipError_t launch_ring(const GemmArgs& a, hipStream_t s) {
   } while (0)
 #define VIT_LAUNCH(EPI)            \
   do {                             \
-    if (half)                      \
+    if (half3)                     \
+      VIT_LAUNCH_NS(EPI, 2, 64);   \
+    else if (half)                 \
       VIT_LAUNCH_NS(EPI, 4, 64);   \
     else if (two)                  \
       VIT_LAUNCH_NS(EPI, 2, 128);  \

@@ -76,9 +76,10 @@ def test_cfg6_6b_downsampled_sampled():
 
 
 def test_tokens_are_bit_identical_at_every_batch_size():
-    """An image's tokens do not depend on how many images share its launch: 1, 2 and 8 images run every
-    product on the ring kernel (four- and two-stage rings; 1 and 2 images with its 64-row tiles for the
-    narrow products), 64 images mix both matrix-product kernels, 260 images run the persistent 256 x 256
+    """An image's tokens do not depend on how many images share its launch: 1, 2, 3 and 8 images run every
+    product on the ring kernel (four- and two-stage rings; 1 to 3 images with its 64-row tiles for the
+    narrow products, 8 images with three two-stage workgroups of 64 rows to a unit for them),
+    64 images mix both matrix-product kernels, 260 images run the persistent 256 x 256
     kernel, and all of them add a token's k-steps in the same order.  Compared bit for bit against the
     full config-3 batch."""
     import torch
@@ -86,13 +87,13 @@ def test_tokens_are_bit_identical_at_every_batch_size():
     import paper_2502_00937_amd as V
 
     cfg, ipr, tpi = _workload("cfg3")
-    say("case batch-size invariance (config-3 model: 260, 64, 8, 2, 1 images)")
+    say("case batch-size invariance (config-3 model: 260, 64, 8, 3, 2, 1 images)")
     enc = V.VitEncoder(cfg, gen.make_weights(cfg, seed=0), device=0)
     px = torch.from_numpy(gen.make_pixels(cfg, 260, seed=1)).cuda()
     T = gen.tokens_per_tile(cfg)
     full, _ = enc.encode(px, ipr, np.arange(261, dtype=np.int32))
     torch.cuda.synchronize()
-    for n in (64, 8, 2, 1):
+    for n in (64, 8, 3, 2, 1):
         part, _ = enc.encode(px[:n], [n], np.arange(n + 1, dtype=np.int32))
         torch.cuda.synchronize()
         same = torch.equal(part.view(torch.int16), full[:n * T].view(torch.int16))
