@@ -117,3 +117,41 @@ def test_buffers_of_more_than_2_31_elements():
     say(f"case 2^31 elements: {sum(tpi)} tiles, {sum(tpi) * T} tokens")
     got, _ = check_case(cfg, tpi, [1] * len(tpi), images=[0, 139], oracle_dtype=np.float32, label="2^31")
     assert got.shape == (sum(tpi) * T, 4096)
+
+
+def test_head_by_head_qkv_buffer_past_4_gib():
+    """Head dim 64 stores the QKV product head by head: 48 blocks of [rows, 64].  With 700 400 token rows (41 200
+    tiles of 17 tokens, hidden 1024 = 16 heads) the buffer is 4.3 GB, so the last heads' blocks start past byte 2^32.
+    One layer, a narrow MLP, no projector: the first and the last image against the oracle, and the last three
+    images encoded alone (every product on the small-tile kernel, a 2 KB QKV buffer) bit for bit."""
+    import torch
+
+    import paper_2502_00937_amd as V
+
+    from oracle import vit_oracle as O
+    from parity_util import assert_parity
+
+    cfg = {"image_size": 56, "patch_size": 14, "channels": 3, "hidden": 1024, "heads": 16, "mlp": 256,
+           "layers_local": 1, "layers_global": 0, "has_cls": 1, "final_ln": 1, "ln_eps": 1e-6, "proj_layers": 0,
+           "proj_dims": (), "dtype": "bf16", "token_merge": 1}
+    n, T = 41200, 17
+    assert gen.tokens_per_tile(cfg) == T and 48 * n * T * 64 * 2 > 2 ** 32
+    say(f"case head-by-head QKV past 4 GiB: {n} tiles, {n * T} tokens")
+    weights = gen.make_weights(cfg, seed=3)
+    px = gen.make_pixels(cfg, n, seed=4)
+    enc = V.VitEncoder(cfg, weights, device=0)
+    try:
+        dpx = torch.from_numpy(px).cuda()
+        full, _ = enc.encode(dpx, [n], np.arange(n + 1, dtype=np.int32))
+        torch.cuda.synchronize()
+        assert full.shape == (n * T, 1024)
+        tail, _ = enc.encode(dpx[n - 3:], [3], np.arange(4, dtype=np.int32))
+        torch.cuda.synchronize()
+        same = torch.equal(tail.view(torch.int16), full[(n - 3) * T:].view(torch.int16))
+        say(f"    last three images alone against the batch: bit-identical = {same}")
+        assert same
+        for i in (0, n - 1):
+            want, _ = O.vit_oracle_encode(cfg, weights, px[i:i + 1], [1], np.array([0, 1], dtype=np.int32))
+            assert_parity(full[i * T:(i + 1) * T].float().cpu().numpy(), want, "bf16", f"4 GiB image {i}")
+    finally:
+        enc.close()
