@@ -4,8 +4,9 @@
 //
 // Everything is computed transposed so that a lane owns one query for the whole kernel:
 //   S^T[key, q]  = K[key, :] . Q[q, :]       (A = K tile from LDS, B = Q^T held in registers)
-//   O^T[d, q]   += V^T[d, key] . P^T[key, q] (A = V^T tile from LDS, B = P^T straight from the
-//                                             S^T accumulator registers)
+//   O^T[d, q]   += V^T[d, key] . P^T[key, q] (A = V^T fragments, taken from the V tile in LDS with the
+//                                             transposing read; B = P^T straight from the S^T
+//                                             accumulator registers)
 // With the 32x32 MFMA accumulator layout (lane = column q, registers = rows) the softmax
 // statistics of a query are per-lane scalars, the row maximum needs one exchange with lane^32,
 // and the P^T operand of the second product is the accumulator of the first, converted in
@@ -24,6 +25,10 @@
 // see `attend` below.
 // K/V tiles of 64 keys are double-buffered in LDS: the next tile's global loads are issued before
 // the current tile is processed and written to the other buffer afterwards (one barrier per tile).
+// Both tiles are stored as they are loaded, whole rows of 16-byte pieces; ds_read_b64_tr_b16 hands the
+// second product its V^T fragments (four keys of one column per lane and instruction).  A V tile
+// transposed on its way into LDS (v_perm_b32 and eight 4-byte stores per 16-byte piece, loads of 16
+// bytes from 32 different rows per instruction) cost the kernel 4 % at head dim 64 and 10 % at 72.
 #include <type_traits>
 
 #include "common.h"
@@ -51,23 +56,19 @@ struct AttnShape {
   static constexpr int DB = (DHP + 31) / 32;     // 32-row blocks of O^T
   static constexpr int NCH = DHP / 8;            // 16-byte chunks per K/V row
   static constexpr int K_STRIDE = DHL * 2 + 16;  // bytes per K row in LDS (padding kills bank conflicts)
-  static constexpr int VT_STRIDE = AKV * 2 + 8;  // bytes per V^T row in LDS
+  // V rows in LDS: the head dim, then the spare rows of the last O^T block as extra columns (zeros, or ones for the
+  // row sums, see SUM).  The second product's V^T fragments are read with the transposing LDS read, whose sixteen
+  // lanes fetch 4 keys x 64 bytes: a row stride of 32 bytes times an odd number puts those four rows on different
+  // banks (head dim 96: 208 bytes, two rows of four share banks, so that three workgroups still fit a unit's LDS).
+  static constexpr int V_COLS = DB * 32;
+  static constexpr int V_STRIDE = DHP == 96 ? 208 : V_COLS * 2 + 32;
   static constexpr int K_BYTES = AKV * K_STRIDE;
-  static constexpr int VT_BYTES = DB * 32 * VT_STRIDE;
-  static constexpr int STAGE = K_BYTES + VT_BYTES;
-  static constexpr int K_ITEMS = AKV * NCH;        // 16-byte chunks of the K tile
-  static constexpr int V_ITEMS = (AKV / 2) * NCH;  // (key pair, chunk) items of the V tile
-  // Item -> (key pair, chunk): blocks of 32 key pairs x CW chunks, the chunk running fastest.  With CW = 4 one load
-  // instruction covers 16 key pairs x 64 bytes where CW = 1 covers 32 x 32 bytes, half the cache lines per
-  // instruction for the unit that turns lane addresses into cache requests (3 % of the kernel), and a half wave's
-  // transposed stores (bank = 16 * chunk + key pair + const) still fall on 32 different banks; with CW = 8 (whole
-  // 128-byte rows per instruction) they collide two by two and the kernel is 4 % slower than with 4: measured.
-  static constexpr int CW = NCH % 4 == 0 ? 4 : NCH % 2 == 0 ? 2 : 1;
-  static __device__ __forceinline__ int v_kp(int it) { return (it % (32 * CW)) / CW; }
-  static __device__ __forceinline__ int v_ch(int it) { return (it / (32 * CW)) * CW + it % CW; }
-  static constexpr int K_PER = (K_ITEMS + ANT - 1) / ANT, V_PER = (V_ITEMS + ANT - 1) / ANT;
+  static constexpr int V_BYTES = AKV * V_STRIDE;
+  static constexpr int STAGE = K_BYTES + V_BYTES;
+  static constexpr int K_ITEMS = AKV * NCH;  // 16-byte chunks of the K tile, and of the V tile
+  static constexpr int K_PER = (K_ITEMS + ANT - 1) / ANT;
   // where the row sums of P come from in the fast pass: spare rows of the last O^T block if the head dim leaves
-  // any (72, 80), vector instructions otherwise (v_dot2c_f32_bf16 of a packed pair with a pair of ones: 8 per
+  // any (72, 80: two columns of ones in the V rows' padding), vector instructions otherwise (v_dot2c_f32_bf16 of a packed pair with a pair of ones: 8 per
   // block of logits).  (One more accumulator fed by a fragment of ones held in registers costs 20 registers: at
   // head dim 64 that is the fourth wave of a SIMD, and the kernel came out 5 % slower with it, 13 % when forced
   // into 128 registers.)
@@ -78,7 +79,7 @@ template <int DHP, int QB, int NW>
 __global__ __launch_bounds__(64 * NW, QB == 1 ? (DHP == 64 ? 4 : DHP <= 96 ? 3 : 2) : 2) void attention_bf16_kernel(const AttnArgs a) {
   using Sh = AttnShape<DHP, QB, NW>;
   constexpr int ANT = Sh::ANT;
-  extern __shared__ __attribute__((aligned(16))) unsigned char lds[];  // 2 stages of (K tile, V^T tile)
+  extern __shared__ __attribute__((aligned(16))) unsigned char lds[];  // 2 stages of (K tile, V tile)
 
   // Workgroup ids are dealt round-robin to the 8 XCDs.  Consecutive work items are the query
   // blocks of one segment, which read the same K and V rows: give each XCD a contiguous run of
@@ -91,6 +92,17 @@ __global__ __launch_bounds__(64 * NW, QB == 1 ? (DHP == 64 ? 4 : DHP <= 96 ? 3 :
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int lq = lane & 31, g = lane >> 5;
   const int partner_addr = (lane ^ 32) << 2;  // ds_bpermute byte address of the lane that holds the other 16 keys of a query
+  // The transposing LDS read (ds_read_b64_tr_b16) works on groups of 16 lanes: lane j of a group points at 8 bytes
+  // (four 16-bit values), and lane i receives value i % 4 of the lanes i / 4, i / 4 + 4, i / 4 + 8 and i / 4 + 12.
+  // A lane (lq, g) of the second product needs V[key0 + 4 g + e][32 b + lq], e = 0 .. 3: with lane j of group G
+  // (lq = 16 (G % 2) + i, g = G / 2) pointing at V[key0 + 4 g + j / 4][32 b + 16 (G % 2) + 4 (j % 4) .. + 3], the
+  // lanes j = i / 4 + 4 e hold exactly the keys key0 + 4 g + e at the four columns that contain this lane's.
+  const uint32_t vt_off = (uint32_t)((4 * (lane >> 5) + ((lane & 15) >> 2)) * Sh::V_STRIDE + (16 * ((lane >> 4) & 1) + 4 * (lane & 3)) * 2);
+  auto read_tr = [](const unsigned char* q) {
+    typedef short v4s __attribute__((ext_vector_type(4)));
+    const v4s v = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) v4s*)q);
+    return __builtin_bit_cast(u32x2, v);
+  };
   // this head's Q, K and V: column blocks of the [rows, ld_qkv] matrix, or (qkv_rows != 0) blocks of their own,
   // [qkv_rows, DHP] each with consecutive rows.  Either way: a base and a row stride.
   const size_t blk = a.qkv_rows ? a.qkv_rows * DHP : (size_t)DHP;  // elements from one head's block to the next
@@ -118,7 +130,7 @@ __global__ __launch_bounds__(64 * NW, QB == 1 ? (DHP == 64 ? 4 : DHP <= 96 ? 3 :
     }
   }
 
-  u32x4 rk[Sh::K_PER], rv0[Sh::V_PER], rv1[Sh::V_PER];
+  u32x4 rk[Sh::K_PER], rv[Sh::K_PER];
   // global -> registers.  Each thread's (row, column) inside a tile is fixed, so its byte offsets
   // are computed once; only a segment's last tile clamps rows past the end to the last row (their
   // logits are masked, the clamped values only need to be finite).
@@ -129,18 +141,13 @@ __global__ __launch_bounds__(64 * NW, QB == 1 ? (DHP == 64 ? 4 : DHP <= 96 ? 3 :
   // computed once, and a full tile is loaded from a wave-uniform base plus those offsets with no
   // address arithmetic at all.  Only a segment's last, partial tile clamps rows past the end to the
   // last row (their logits are masked, the clamped values only need to be finite).
-  uint32_t k_off[Sh::K_PER], v_off[Sh::V_PER];
+  uint32_t k_off[Sh::K_PER];  // (V rows are read at the same offsets from their own base)
 #pragma unroll
   // (threads whose item index lies past the tile's last item load the last item again and do not
   //  store it: no load sits under divergent control flow)
   for (int i = 0; i < Sh::K_PER; ++i) {
     const int it = min(tid + i * ANT, Sh::K_ITEMS - 1), key = it / Sh::NCH;
     k_off[i] = (uint32_t)key * row_bytes + (uint32_t)((it - key * Sh::NCH) * 8) * 2u;
-  }
-#pragma unroll
-  for (int i = 0; i < Sh::V_PER; ++i) {
-    const int it = min(tid + i * ANT, Sh::V_ITEMS - 1);
-    v_off[i] = (uint32_t)(2 * Sh::v_kp(it)) * row_bytes + (uint32_t)(Sh::v_ch(it) * 8) * 2u;
   }
   auto load_tile = [&](int k0, auto partial_tag) {
     constexpr bool PARTIAL = decltype(partial_tag)::value;
@@ -156,41 +163,18 @@ __global__ __launch_bounds__(64 * NW, QB == 1 ? (DHP == 64 ? 4 : DHP <= 96 ? 3 :
         off -= (uint32_t)(key - min(key, last)) * row_bytes;
       }
       rk[i] = *(const u32x4*)(tile_k + off);
-    }
-#pragma unroll
-    for (int i = 0; i < Sh::V_PER; ++i) {
-      const int it = min(tid + i * ANT, Sh::V_ITEMS - 1);
-      uint32_t o0 = v_off[i], o1 = v_off[i] + row_bytes;
-      if (PARTIAL) {
-        const int r = 2 * Sh::v_kp(it);
-        o0 -= (uint32_t)(r - min(r, last)) * row_bytes;
-        o1 -= (uint32_t)(r + 1 - min(r + 1, last)) * row_bytes;
-      }
-      rv0[i] = *(const u32x4*)(tile_v + o0);
-      rv1[i] = *(const u32x4*)(tile_v + o1);
+      rv[i] = *(const u32x4*)(tile_v + off);
     }
   };
-  // registers -> LDS; V is transposed on the way in: V^T[d][2kp], V^T[d][2kp+1] packed into one word
-  auto store_tile = [&](unsigned char* sK, unsigned char* sVt) {
+  // registers -> LDS, K and V rows alike (the second product reads V through the transposing LDS read)
+  auto store_tile = [&](unsigned char* sK, unsigned char* sV) {
 #pragma unroll
     for (int i = 0; i < Sh::K_PER; ++i) {
       const int it = tid + i * ANT;
       if (Sh::K_ITEMS % ANT == 0 || it < Sh::K_ITEMS) {
         const int key = it / Sh::NCH, ch = it - key * Sh::NCH;
         *(u32x4*)(sK + key * Sh::K_STRIDE + ch * 16) = rk[i];
-      }
-    }
-#pragma unroll
-    for (int i = 0; i < Sh::V_PER; ++i) {
-      const int it = tid + i * ANT;
-      if (Sh::V_ITEMS % ANT == 0 || it < Sh::V_ITEMS) {
-        const int ch = Sh::v_ch(it), kp = Sh::v_kp(it);
-#pragma unroll
-        for (int e = 0; e < 4; ++e) {
-          const uint32_t x0 = rv0[i][e], x1 = rv1[i][e];  // v_perm_b32: bytes 0-3 = x0, 4-7 = x1
-          *(uint32_t*)(sVt + (ch * 8 + 2 * e) * Sh::VT_STRIDE + kp * 4) = __builtin_amdgcn_perm(x1, x0, 0x05040100u);
-          *(uint32_t*)(sVt + (ch * 8 + 2 * e + 1) * Sh::VT_STRIDE + kp * 4) = __builtin_amdgcn_perm(x1, x0, 0x07060302u);
-        }
+        *(u32x4*)(sV + key * Sh::V_STRIDE + ch * 16) = rv[i];
       }
     }
   };
@@ -200,24 +184,24 @@ __global__ __launch_bounds__(64 * NW, QB == 1 ? (DHP == 64 ? 4 : DHP <= 96 ? 3 :
   const bool wave_active = w.q0 + wave * QB * 32 < seg_end;
 
   // What the loader never writes must still be finite (a product with garbage could be NaN): the K rows' columns
-  // DHP .. DHL - 1 take part in S^T and are zero.  The V^T rows DHP .. 32 DB - 1 only produce O^T rows that are
+  // DHP .. DHL - 1 take part in S^T and are zero.  The V rows' columns DHP .. 32 DB - 1 only produce O^T rows that are
   // never stored; they are zero, except that with SUM_ROWS two of them hold ones, so that the row sums of P come
-  // out of the second product for nothing (row DHP for the lanes with g = 0, row DHP + 4 for those with g = 1:
-  // the same accumulator register).  Both stages, once.
+  // out of the second product for nothing (column DHP for the lanes with g = 0, column DHP + 4 for those with
+  // g = 1: the same accumulator register).  Both stages, once.
   if constexpr (Sh::DHL > DHP || Sh::DB * 32 > DHP) {
 #pragma unroll
     for (int stg = 0; stg < 2; ++stg) {
       unsigned char* sK = lds + stg * Sh::STAGE;
-      unsigned char* sVt = sK + Sh::K_BYTES;
+      unsigned char* sV = sK + Sh::K_BYTES;
       if constexpr (Sh::DHL > DHP) {
         static_assert(Sh::DHL - DHP == 8 || Sh::DHL == DHP, "at most one 16-byte chunk of padding per K row");
         for (int key = tid; key < AKV; key += ANT) *(u32x4*)(sK + key * Sh::K_STRIDE + DHP * 2) = u32x4{0u, 0u, 0u, 0u};
       }
-      constexpr int PAD_ROWS = Sh::DB * 32 - DHP, WORDS = AKV / 2;  // 4-byte words per V^T row
-      for (int it = tid; it < PAD_ROWS * WORDS; it += ANT) {
-        const int r = it / WORDS;
-        const uint32_t fill = Sh::SUM == SUM_ROWS && (r == 0 || r == 4) ? 0x3F803F80u : 0u;  // two bf16 ones
-        *(uint32_t*)(sVt + (DHP + r) * Sh::VT_STRIDE + (it % WORDS) * 4) = fill;
+      constexpr int PAD_WORDS = (Sh::V_COLS - DHP) / 2;  // 4-byte words of padding per V row
+      for (int it = tid; it < AKV * PAD_WORDS; it += ANT) {
+        const int key = it / PAD_WORDS, wd = it % PAD_WORDS;  // word wd holds columns DHP + 2 wd and DHP + 2 wd + 1
+        const uint32_t fill = Sh::SUM == SUM_ROWS && (wd == 0 || wd == 2) ? 0x00003F80u : 0u;  // a bf16 one, a zero
+        *(uint32_t*)(sV + key * Sh::V_STRIDE + DHP * 2 + wd * 4) = fill;
       }
     }
   }
@@ -235,7 +219,7 @@ __global__ __launch_bounds__(64 * NW, QB == 1 ? (DHP == 64 ? 4 : DHP <= 96 ? 3 :
   // is checked once, after the last tile; a workgroup with a row outside runs the general pass instead.  Per
   // 32 x 32 block of logits this pass issues 16 exp2, 8 packed conversions and its MFMAs; the row sums come from
   // the matrix cores where the head dim leaves spare rows in the last O^T block (SUM_ROWS: two rows of ones in the
-  // V^T tile's padding), else from 8 two-element dot products with ones (SUM_VALU).  Either way the sum is taken
+  // V tile's padding), else from 8 two-element dot products with ones (SUM_VALU).  Either way the sum is taken
   // over the rounded weights, the ones the second product multiplies with.
   //
   // General pass: the online softmax with a lazily moving reference maximum m.  m only has to keep exp2 in range,
@@ -264,7 +248,7 @@ __global__ __launch_bounds__(64 * NW, QB == 1 ? (DHP == 64 ? 4 : DHP <= 96 ? 3 :
     auto process_tile = [&](int t, auto mask_tag) {
       constexpr bool MASK = decltype(mask_tag)::value;
       const unsigned char* sK = lds + (t & 1) * Sh::STAGE;
-      const unsigned char* sVt = sK + Sh::K_BYTES;
+      const unsigned char* sV = sK + Sh::K_BYTES;
       if (t + 1 < n_tiles) {  // the next tile is full unless it is the segment's last, partial one
         if ((t + 2) * AKV <= w.seg_len) load_tile((t + 1) * AKV, std::false_type{});
         else load_tile((t + 1) * AKV, std::true_type{});
@@ -356,8 +340,9 @@ __global__ __launch_bounds__(64 * NW, QB == 1 ? (DHP == 64 ? 4 : DHP <= 96 ? 3 :
         for (int b = 0; b < Sh::DB; ++b)
 #pragma unroll
           for (int s2 = 0; s2 < 2; ++s2) {
-            const unsigned char* p = sVt + (b * 32 + lq) * Sh::VT_STRIDE + (kb * 32 + s2 * 16 + 4 * g) * 2;
-            const u32x2 lo = *(const u32x2*)p, hi = *(const u32x2*)(p + 16);
+            // V^T[32 b + lq][keys 32 kb + 16 s2 + 4 g .. + 3] and the same eight keys on: two transposing reads
+            const unsigned char* p = sV + (kb * 32 + s2 * 16) * Sh::V_STRIDE + b * 64 + vt_off;
+            const u32x2 lo = read_tr(p), hi = read_tr(p + 8 * Sh::V_STRIDE);
             const u32x4 packed = {lo[0], lo[1], hi[0], hi[1]};
             const bf16x8 vf = __builtin_bit_cast(bf16x8, packed);
 #pragma unroll
