@@ -57,11 +57,14 @@ struct AttnShape {
   static constexpr int NCH = DHP / 8;            // 16-byte chunks per K/V row
   static constexpr int K_STRIDE = DHL * 2 + 16;  // bytes per K row in LDS (padding kills bank conflicts)
   // V rows in LDS: the head dim, then the spare rows of the last O^T block as extra columns (zeros, or ones for the
-  // row sums, see SUM).  The second product's V^T fragments are read with the transposing LDS read, whose sixteen
-  // lanes fetch 4 keys x 64 bytes: a row stride of 32 bytes times an odd number puts those four rows on different
-  // banks (head dim 96: 208 bytes, two rows of four share banks, so that three workgroups still fit a unit's LDS).
+  // row sums, see SUM).  The second product's V^T fragments are read with the transposing LDS read; half a wave
+  // fetches 4 keys x 64 bytes at a time, which fall on the 64 banks once each when the row stride is 64 bytes
+  // times an odd number (192 bytes for the head dims with 96 columns, 320 for 128).  Head dim 64 would need 192
+  // bytes for its 128, and four workgroups would no longer fit a unit's LDS: its rows are 128 bytes with no padding,
+  // and the rows of every second pair of keys keep their two 64-byte halves swapped (V_SWAP), which does the same.
   static constexpr int V_COLS = DB * 32;
-  static constexpr int V_STRIDE = DHP == 96 ? 208 : V_COLS * 2 + 32;
+  static constexpr bool V_SWAP = DHP == 64;
+  static constexpr int V_STRIDE = V_SWAP ? 128 : ((V_COLS * 2 + 63) / 64 | 1) * 64;
   static constexpr int K_BYTES = AKV * K_STRIDE;
   static constexpr int V_BYTES = AKV * V_STRIDE;
   static constexpr int STAGE = K_BYTES + V_BYTES;
@@ -97,7 +100,10 @@ __global__ __launch_bounds__(64 * NW, QB == 1 ? (DHP == 64 ? 4 : DHP <= 96 ? 3 :
   // A lane (lq, g) of the second product needs V[key0 + 4 g + e][32 b + lq], e = 0 .. 3: with lane j of group G
   // (lq = 16 (G % 2) + i, g = G / 2) pointing at V[key0 + 4 g + j / 4][32 b + 16 (G % 2) + 4 (j % 4) .. + 3], the
   // lanes j = i / 4 + 4 e hold exactly the keys key0 + 4 g + e at the four columns that contain this lane's.
+  // (V_SWAP: the lane's key is key0 + 4 g + j / 4 with key0 a multiple of 8, so bit 1 of the key is bit 3 of j, and
+  //  the swap turns column block b into b ^ 1 for those lanes)
   const uint32_t vt_off = (uint32_t)((4 * (lane >> 5) + ((lane & 15) >> 2)) * Sh::V_STRIDE + (16 * ((lane >> 4) & 1) + 4 * (lane & 3)) * 2);
+  const uint32_t vt_swap = Sh::V_SWAP && (lane & 8) ? 64u : 0u;
   auto read_tr = [](const unsigned char* q) {
     typedef short v4s __attribute__((ext_vector_type(4)));
     const v4s v = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) v4s*)q);
@@ -174,7 +180,7 @@ __global__ __launch_bounds__(64 * NW, QB == 1 ? (DHP == 64 ? 4 : DHP <= 96 ? 3 :
       if (Sh::K_ITEMS % ANT == 0 || it < Sh::K_ITEMS) {
         const int key = it / Sh::NCH, ch = it - key * Sh::NCH;
         *(u32x4*)(sK + key * Sh::K_STRIDE + ch * 16) = rk[i];
-        *(u32x4*)(sV + key * Sh::V_STRIDE + ch * 16) = rv[i];
+        *(u32x4*)(sV + key * Sh::V_STRIDE + (Sh::V_SWAP && (key & 2) ? ch ^ 4 : ch) * 16) = rv[i];
       }
     }
   };
@@ -341,7 +347,7 @@ __global__ __launch_bounds__(64 * NW, QB == 1 ? (DHP == 64 ? 4 : DHP <= 96 ? 3 :
 #pragma unroll
           for (int s2 = 0; s2 < 2; ++s2) {
             // V^T[32 b + lq][keys 32 kb + 16 s2 + 4 g .. + 3] and the same eight keys on: two transposing reads
-            const unsigned char* p = sV + (kb * 32 + s2 * 16) * Sh::V_STRIDE + b * 64 + vt_off;
+            const unsigned char* p = sV + (kb * 32 + s2 * 16) * Sh::V_STRIDE + ((uint32_t)(b * 64) ^ vt_swap) + vt_off;
             const u32x2 lo = read_tr(p), hi = read_tr(p + 8 * Sh::V_STRIDE);
             const u32x4 packed = {lo[0], lo[1], hi[0], hi[1]};
             const bf16x8 vf = __builtin_bit_cast(bf16x8, packed);
