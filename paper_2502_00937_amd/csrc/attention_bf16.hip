@@ -224,7 +224,7 @@ __global__ __launch_bounds__(64 * NW, QB == 1 ? (DHP == 64 ? 4 : DHP <= 96 ? 3 :
   // 2^-100 and 2^100, i.e. while the largest logit of a row lies within about +-69 (natural units) of zero.  That
   // is checked once, after the last tile; a workgroup with a row outside runs the general pass instead.  Per
   // 32 x 32 block of logits this pass issues 16 exp2, 8 packed conversions and its MFMAs; the row sums come from
-  // the matrix cores where the head dim leaves spare rows in the last O^T block (SUM_ROWS: two rows of ones in the
+  // the matrix cores where the head dim leaves spare rows in the last O^T block (SUM_ROWS: two columns of ones in the
   // V tile's padding), else from 8 two-element dot products with ones (SUM_VALU).  Either way the sum is taken
   // over the rounded weights, the ones the second product multiplies with.
   //
